@@ -1,0 +1,202 @@
+/*
+ * pygraph_hip.h -- C ABI of libpygraph_hip: capture a chain of short GPU kernels once into a
+ * hipGraph and replay it with fresh inputs, on one MI355X (gfx950).
+ *
+ * The problem (paper, Sec. 2.1-2.2): an iteration launches hundreds of short dependent kernels;
+ * launching each from the CPU leaves the GPU idle, a graph replays them with one dispatch, but a
+ * graph freezes kernel arguments at capture.  Three ways to give a replay its fresh inputs:
+ *   - PG_GRAPH_COPY      copy every external input into a static placeholder the graph reads
+ *                        (Sec. 2.2 "Cost-benefit analysis", Sec. 4 "Graph-Capture Layer");
+ *   - PG_GRAPH_INDIRECT  Parameter Indirection (Sec. 3, Sec. 4 "Kernel generation"): kernels take
+ *                        a pointer to a pointer, the replay rewrites 8 bytes per input;
+ *   - selection          Selective graphs (Sec. 3, Sec. 4.3): per graph (here: per segment of the
+ *                        chain) keep the fastest of {no graph, graph, graph + indirection}.
+ *
+ * Conventions
+ *   - Every function returns a pg_status (0 = success), never aborts, never throws.  The text of
+ *     the last error of the calling thread is pg_last_error(); the last HIP error code is
+ *     pg_last_hip_error().
+ *   - Pointers marked [dev] are device addresses, [host] host addresses.  The CALLER owns all
+ *     device memory: external inputs, weights and one workspace blob.  The library borrows them,
+ *     carves the workspace (placeholders, internal buffers, pointer table, copy job list; each
+ *     sub-buffer 256-byte aligned), and allocates or frees no device memory itself.  It owns only
+ *     host objects (descriptors, graphs, pinned staging).
+ *   - Weights and the workspace must stay alive and unmoved until pg_chain_destroy.  External
+ *     tensors must stay alive until the stream has finished the call that received them.  Freeing
+ *     one earlier is the dangling-capture crash the paper describes (Sec. 1); it is not detected.
+ *   - Calls that take a stream only enqueue work on it; the caller synchronises.  The stream
+ *     must be a created (non-NULL) stream that is not capturing.  hip_stream is a hipStream_t.
+ *   - External inputs are read-only to the chain; a kernel writes internal buffers only.
+ *   - A chain object is not thread-safe; distinct chains may be used from distinct threads.
+ */
+#ifndef PYGRAPH_HIP_H
+#define PYGRAPH_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PG_OK = 0,
+    PG_EINVAL = 1,   /* bad argument or malformed descriptor */
+    PG_ESTATE = 2,   /* call out of order (replay before capture, ...) */
+    PG_EHIP = 3,     /* a HIP call failed; code in pg_last_hip_error() */
+    PG_ENOMEM = 4,   /* workspace too small */
+    PG_EUNAVAIL = 5  /* the mode does not exist for this segment */
+} pg_status;
+
+typedef enum { PG_F32 = 0, PG_BF16 = 1 } pg_dtype;
+
+/* The chain's kernels.  fp32 arithmetic inside, one rounding to the storage dtype at the store. */
+typedef enum {
+    PG_ADD = 0,             /* o[i] = a[i] + b[i mod m]                                   */
+    PG_MUL = 1,             /* o[i] = a[i] * b[i mod m]                                   */
+    PG_GELU = 2,            /* o[i] = a[i] * Phi(a[i]), Phi the normal CDF (erf form)     */
+    PG_RMSNORM = 3,         /* o[r,i] = x[r,i] * rsqrt(mean_i x[r,i]^2 + eps) * g[i]      */
+    PG_GEMV = 4,            /* y[r,j] = sum_i W[j,i] * h[r,i]; W row-major [n, cols]      */
+    PG_SCALE_BIAS_RELU = 5  /* o[b,c,p] = max(0, x[b,c,p]*s[c] + b[c]); x is [N,C,inner]  */
+} pg_op;
+
+/* Execution variants of a segment; the order is the tie-break order of pg_select. */
+typedef enum { PG_EAGER = 0, PG_GRAPH_COPY = 1, PG_GRAPH_INDIRECT = 2 } pg_mode;
+
+/* Where an operand lives (paper, Sec. 4 "Graph-Capture Layer": externally supplied parameters
+ * need a refresh per replay, parameters produced inside the graph do not). */
+typedef enum { PG_REF_NONE = 0, PG_REF_EXT = 1, PG_REF_INT = 2, PG_REF_WEIGHT = 3 } pg_ref_kind;
+
+typedef struct { int32_t kind; int32_t index; } pg_ref;
+typedef struct { int32_t dtype; int32_t reserved; int64_t numel; } pg_tensor_desc;
+
+typedef struct {
+    int32_t op;        /* pg_op */
+    int32_t dtype;     /* pg_dtype of every operand and of the output */
+    int32_t segment;   /* non-decreasing along the chain, starting at 0, no gaps */
+    int32_t reserved;
+    pg_ref out;        /* must be PG_REF_INT */
+    pg_ref in[3];      /* ADD/MUL: a, b | GELU: a | RMSNORM: x, g | GEMV: W, h | SCALE_BIAS_RELU: x, s, b */
+    int64_t n;         /* output elements (per row for RMSNORM and GEMV) */
+    int64_t m;         /* ADD/MUL: period of b (0 means n); m <= numel(b) */
+    int64_t rows;      /* RMSNORM/GEMV: batch rows */
+    int64_t cols;      /* GEMV: input width; RMSNORM: hidden size (== n) */
+    int64_t inner;     /* SCALE_BIAS_RELU: H*W; channels = numel(s) = numel(b); n % (channels*inner) == 0 */
+    float eps;         /* RMSNORM */
+    int32_t reserved2;
+} pg_kernel_desc;
+
+typedef struct pg_chain pg_chain;
+
+typedef struct {
+    int32_t n_kernels, n_segments, n_ext, n_ext_reading_kernels;
+    int64_t copy_bytes_per_replay;   /* sum of external tensor bytes (payload of a copy refresh) */
+    int64_t table_bytes_per_replay;  /* 8 * n_ext (payload of an indirect refresh)               */
+    int64_t workspace_bytes;
+    int32_t copy_chunks;             /* work items of the batched copy kernel                    */
+    int32_t captured;                /* 1 after pg_capture                                       */
+} pg_stats;
+
+/* How pg_replay_indirect moves the pointers host -> device (paper, Sec. 4 "Graph-Capture
+ * Layer": pointer copies are host-to-device transfers, unlike the device-to-device data copies). */
+typedef enum {
+    PG_TABLE_KERNARG = 0,  /* a one-wave kernel whose argument block carries the pointers      */
+    PG_TABLE_MEMCPY = 1    /* hipMemcpyAsync from a ring of pinned staging slots               */
+} pg_table_refresh;
+
+/* Bytes of workspace [dev] a chain needs.  Host only.  The descriptor is validated as in
+ * pg_chain_build as far as that is possible without the weight descriptors.  ext / ints: [host]
+ * arrays of n_ext / n_int tensor descriptors. */
+pg_status pg_chain_workspace_bytes(const pg_kernel_desc *kernels, int32_t n_kernels,
+                                   const pg_tensor_desc *ext, int32_t n_ext,
+                                   const pg_tensor_desc *ints, int32_t n_int, size_t *bytes_out);
+
+/* Build a chain: validate the descriptor, lay out the workspace, resolve kernels and launch
+ * shapes.  Host only: touches no device memory, makes no HIP call.
+ *   kernels [host]         n_kernels descriptors, copied.
+ *   weight_dev_ptrs [host] array of n_w device pointers [dev], each aligned to 16 bytes.
+ *   workspace_dev [dev]    256-byte aligned, >= pg_chain_workspace_bytes; contents undefined.
+ * Rules checked (PG_EINVAL otherwise): indices in range; sizes positive and consistent with the
+ * tensor descriptors; every read of an internal buffer lies inside what an earlier kernel of the
+ * chain wrote (so no state leaks from one replay into the next); out may alias in[0] exactly
+ * (in-place) for ADD/MUL/GELU/SCALE_BIAS_RELU only and must not overlap any other operand. */
+pg_status pg_chain_build(const pg_kernel_desc *kernels, int32_t n_kernels,
+                         const pg_tensor_desc *ext, int32_t n_ext,
+                         const pg_tensor_desc *ints, int32_t n_int,
+                         const void *const *weight_dev_ptrs, const pg_tensor_desc *weights, int32_t n_w,
+                         void *workspace_dev, size_t workspace_bytes, pg_chain **out);
+
+/* Capture (paper, Sec. 2.2 stream capture; Sec. 4 "Graph-Capture Layer"): for every segment record
+ * its kernels on `hip_stream` twice -- once reading the static placeholders, once reading the
+ * pointer table -- instantiate and upload the graphs, and write the static part of the copy
+ * kernel's job list into the workspace.  Synchronises the stream before returning.  Calling it
+ * again re-captures. */
+pg_status pg_capture(pg_chain *chain, void *hip_stream);
+
+/* One iteration, kernel by kernel from the host with the caller's pointers (the no-graph
+ * baseline, Sec. 2.1).  ext_dev_ptrs [host]: n_ext device pointers [dev], each aligned to its
+ * element size; 16-byte aligned pointers take the vector path. */
+pg_status pg_eager(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+
+/* Kernels [k_begin, k_end) of the chain, launched eagerly as in pg_eager; internal buffers keep
+ * whatever earlier calls left in them.  For stepping through a chain kernel by kernel (tests compare
+ * each kernel's output with the CPU reference applied to that kernel's actual inputs). */
+pg_status pg_eager_range(pg_chain *chain, const void *const *ext_dev_ptrs, int32_t k_begin, int32_t k_end,
+                         void *hip_stream);
+
+/* One iteration: one launch of the batched copy kernel (external tensors -> placeholders, device
+ * to device), then one graph launch per segment (Sec. 4 "Graph-Capture Layer", baseline). */
+pg_status pg_replay_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+
+/* One iteration: write the n_ext pointers into the device-resident table (8 bytes each), then one
+ * graph launch per segment; kernels dereference their table slots first (Sec. 3, Sec. 4). */
+pg_status pg_replay_indirect(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+
+/* Selection rule (Sec. 4.3): mode_out[s] = the available variant of least cost, each segment on
+ * its own.  cost_us [host] is [n_seg][3] in pg_mode order; a non-finite entry marks a variant that
+ * does not exist; ties keep the earlier mode.  A negative cost or a segment with no variant is
+ * PG_EINVAL.  Pure function: no chain, no device, deterministic. */
+pg_status pg_select(const double *cost_us, int32_t n_seg, uint8_t *mode_out);
+
+/* Slow-path profiler (Sec. 3 "Selective CUDA Graphs"): time every (segment, mode) on the given
+ * inputs and fill cost_us_out [host] [n_seg][3] with the median microseconds over `iters`
+ * samples (each sample: `inner` back-to-back runs then one stream synchronisation).  A segment
+ * that reads no external operand reports PG_GRAPH_INDIRECT as NaN: it would be the same graph. */
+pg_status pg_profile(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream,
+                     int32_t iters, int32_t inner, double *cost_us_out);
+
+/* One iteration with a per-segment mode (mode [host], n_segments entries of pg_mode).  A copy-mode
+ * segment refreshes the placeholders of the externals it reads; the pointer table is written once
+ * per call if any segment is indirect.  PG_EUNAVAIL if a mode does not exist for its segment. */
+pg_status pg_run_selected(pg_chain *chain, const uint8_t *mode, const void *const *ext_dev_ptrs,
+                          void *hip_stream);
+
+/* The two refresh steps on their own (what pg_replay_copy / pg_replay_indirect do before the
+ * graph launches); for measuring the copy kernel and the table write in isolation. */
+pg_status pg_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+pg_status pg_refresh_indirect(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+
+/* Timed loop for benchmarks: `iters` iterations of one mode (pg_mode, or 3 = pg_run_selected with
+ * `mode_per_segment`), iteration t using pointer set t % n_sets of ext_sets [host]
+ * ([n_sets][n_ext] device pointers), one stream synchronisation at the end; returns mean
+ * microseconds per iteration measured on the host clock. */
+pg_status pg_time_loop(pg_chain *chain, int32_t mode, const uint8_t *mode_per_segment,
+                       const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
+                       double *us_per_iter_out);
+
+/* Accessors.  Host only. */
+pg_status pg_chain_int_buffer(const pg_chain *chain, int32_t int_index, void **dev_ptr_out, size_t *bytes_out);
+pg_status pg_chain_placeholder(const pg_chain *chain, int32_t ext_index, void **dev_ptr_out, size_t *bytes_out);
+pg_status pg_chain_pointer_table(const pg_chain *chain, void **dev_ptr_out, size_t *bytes_out);
+pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);
+pg_status pg_set_table_refresh(pg_chain *chain, int32_t how /* pg_table_refresh */);
+void pg_chain_destroy(pg_chain *chain);
+
+const char *pg_last_error(void);
+int pg_last_hip_error(void);
+const char *pg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

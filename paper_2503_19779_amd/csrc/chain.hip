@@ -1,0 +1,754 @@
+// chain.hip -- chain runtime and C ABI of libpygraph_hip (see include/pygraph_hip.h).
+//
+// A chain is a linear kernel-launch DAG.  The runtime keeps, per kernel, three argument blocks:
+// one for eager launches (external operands patched with the caller's pointers on every call),
+// one whose external operands are static placeholders (graph + copy refresh), and one whose
+// external operands are pointer-table slots (graph + Parameter Indirection).  Graphs are made by
+// stream capture, once per segment and per graph mode.
+#include "../../include/pygraph_hip.h"
+#include "kernels.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_err;
+thread_local int g_hip_err = 0;
+
+pg_status fail(pg_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return st;
+}
+
+#define PG_HIP(call)                                                                               \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            g_hip_err = (int)e_;                                                                   \
+            return fail(PG_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));                   \
+        }                                                                                          \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+size_t elem_bytes(int dtype) { return dtype == PG_F32 ? 4 : 2; }
+
+union ArgBlock {
+    pgk::EwArgs ew;
+    pgk::RmsArgs rms;
+    pgk::GemvArgs gemv;
+    pgk::SbrArgs sbr;
+    // every block starts with: out, in0, in1, (in2)
+    const void* ptr[4];
+};
+
+struct KernelRec {
+    pgk::Launch direct, indirect;   // same shape, different kernel variant
+    ArgBlock a_eager, a_copy, a_ind;
+    int n_in = 0;
+    int ind_mask = 0;               // operands that are external
+    int ext_of[3] = {-1, -1, -1};
+};
+
+struct CopyList {                   // one refresh job: a set of external tensors -> placeholders
+    std::vector<int> ext;           // external indices, ascending
+    std::vector<pgk::CopyTensor> tensors;
+    std::vector<pgk::CopyChunk> chunks;     // sorted by tensor
+    struct Group { int t0, t1, c0, c1; };   // tensors [t0,t1) of this list <-> chunks [c0,c1)
+    std::vector<Group> groups;
+    size_t tensors_off = 0, chunks_off = 0; // in the workspace
+    long long bytes = 0;
+};
+
+struct Segment {
+    int k0 = 0, k1 = 0;
+    bool has_ext = false;
+    int copy_list = -1;             // index into copy_lists
+    hipGraph_t g_copy = nullptr, g_ind = nullptr;
+    hipGraphExec_t x_copy = nullptr, x_ind = nullptr;
+};
+
+}  // namespace
+
+struct pg_chain {
+    std::vector<pg_kernel_desc> k;
+    std::vector<pg_tensor_desc> ext, ints, w;
+    std::vector<const void*> wptr;
+    char* ws = nullptr;
+    size_t ws_bytes = 0, ws_need = 0;
+    std::vector<size_t> ph_off, int_off;
+    size_t table_off = 0;
+    std::vector<KernelRec> rec;
+    std::vector<Segment> seg;
+    std::vector<CopyList> copy_lists;   // [0] = all externals; then one per segment that has any
+    std::vector<std::pair<int, int>> eager_fix;   // (kernel, operand) pairs that take a caller pointer
+    bool captured = false;
+    int table_how = PG_TABLE_KERNARG;
+    // pinned staging ring for PG_TABLE_MEMCPY
+    static constexpr int kRing = 64;
+    void* staging = nullptr;
+    size_t staging_stride = 0;
+    unsigned long long ring_cnt = 0;
+    hipEvent_t ring_ev[2] = {nullptr, nullptr};
+    bool ring_used[2] = {false, false};
+};
+
+namespace {
+
+// ---- descriptor validation and layout ------------------------------------------------------------
+struct Layout {
+    std::vector<size_t> ph_off, int_off;
+    size_t table_off = 0;
+    std::vector<CopyList> lists;
+    std::vector<Segment> seg;
+    size_t total = 0;
+};
+
+int n_inputs(int op) {
+    switch (op) {
+    case PG_ADD: case PG_MUL: case PG_RMSNORM: case PG_GEMV: return 2;
+    case PG_GELU: return 1;
+    case PG_SCALE_BIAS_RELU: return 3;
+    default: return -1;
+    }
+}
+
+bool fits_i32(long long v) { return v > 0 && v <= 0x7fffffffll; }
+
+pg_status validate(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int n_ext,
+                   const pg_tensor_desc* ints, int n_int, const pg_tensor_desc* w, int n_w) {
+    if (!k || nk <= 0) return fail(PG_EINVAL, "no kernels");
+    if (n_ext < 0 || n_int <= 0 || n_w < 0) return fail(PG_EINVAL, "bad tensor counts");
+    if ((n_ext && !ext) || !ints || (n_w && !w)) return fail(PG_EINVAL, "null tensor descriptor array");
+    auto chk_desc = [&](const pg_tensor_desc* d, int n, const char* what) -> pg_status {
+        for (int i = 0; i < n; i++) {
+            if (d[i].dtype != PG_F32 && d[i].dtype != PG_BF16) return fail(PG_EINVAL, "%s %d: bad dtype", what, i);
+            if (d[i].numel <= 0 || d[i].numel > (1ll << 40)) return fail(PG_EINVAL, "%s %d: bad numel", what, i);
+        }
+        return PG_OK;
+    };
+    pg_status st;
+    if ((st = chk_desc(ext, n_ext, "ext")) || (st = chk_desc(ints, n_int, "int")) || (st = chk_desc(w, n_w, "weight"))) return st;
+
+    std::vector<long long> written(n_int, 0);   // elements of each internal buffer written so far
+    int seg = 0;
+    for (int i = 0; i < nk; i++) {
+        const pg_kernel_desc& d = k[i];
+        const int nin = n_inputs(d.op);
+        if (nin < 0) return fail(PG_EINVAL, "kernel %d: bad op %d", i, d.op);
+        if (d.dtype != PG_F32 && d.dtype != PG_BF16) return fail(PG_EINVAL, "kernel %d: bad dtype", i);
+        if (i == 0 ? d.segment != 0 : (d.segment != seg && d.segment != seg + 1))
+            return fail(PG_EINVAL, "kernel %d: segment %d breaks the non-decreasing, gap-free order", i, d.segment);
+        seg = d.segment;
+        if (d.out.kind != PG_REF_INT || d.out.index < 0 || d.out.index >= n_int)
+            return fail(PG_EINVAL, "kernel %d: output must be an internal buffer in range", i);
+        if (ints[d.out.index].dtype != d.dtype) return fail(PG_EINVAL, "kernel %d: output dtype mismatch", i);
+        long long numel_in[3] = {0, 0, 0};
+        for (int j = 0; j < 3; j++) {
+            const pg_ref& r = d.in[j];
+            if (j >= nin) {
+                if (r.kind != PG_REF_NONE) return fail(PG_EINVAL, "kernel %d: operand %d must be unused", i, j);
+                continue;
+            }
+            const pg_tensor_desc* t = nullptr;
+            if (r.kind == PG_REF_EXT && r.index >= 0 && r.index < n_ext) t = &ext[r.index];
+            else if (r.kind == PG_REF_INT && r.index >= 0 && r.index < n_int) t = &ints[r.index];
+            else if (r.kind == PG_REF_WEIGHT && r.index >= 0 && r.index < n_w) t = &w[r.index];
+            if (!t) return fail(PG_EINVAL, "kernel %d: operand %d reference out of range", i, j);
+            if (t->dtype != d.dtype) return fail(PG_EINVAL, "kernel %d: operand %d dtype mismatch", i, j);
+            numel_in[j] = t->numel;
+            if (r.kind == PG_REF_INT && r.index == d.out.index) {
+                const bool inplace_ok = j == 0 && (d.op == PG_ADD || d.op == PG_MUL || d.op == PG_GELU || d.op == PG_SCALE_BIAS_RELU);
+                if (!inplace_ok) return fail(PG_EINVAL, "kernel %d: output overlaps operand %d", i, j);
+            }
+        }
+        long long need[3] = {0, 0, 0}, out_need = 0;
+        switch (d.op) {
+        case PG_ADD: case PG_MUL: {
+            const long long m = d.m ? d.m : d.n;
+            if (d.n <= 0 || m <= 0) return fail(PG_EINVAL, "kernel %d: n and m must be positive", i);
+            need[0] = d.n; need[1] = m; out_need = d.n;
+            break;
+        }
+        case PG_GELU:
+            if (d.n <= 0) return fail(PG_EINVAL, "kernel %d: n must be positive", i);
+            need[0] = d.n; out_need = d.n;
+            break;
+        case PG_RMSNORM:
+            if (!fits_i32(d.rows) || !fits_i32(d.cols) || d.n != d.cols) return fail(PG_EINVAL, "kernel %d: bad rows/cols (n must equal cols)", i);
+            if (!(d.eps >= 0.f)) return fail(PG_EINVAL, "kernel %d: eps must be >= 0", i);
+            need[0] = d.rows * d.cols; need[1] = d.cols; out_need = d.rows * d.cols;
+            break;
+        case PG_GEMV:
+            if (!fits_i32(d.rows) || !fits_i32(d.cols) || !fits_i32(d.n)) return fail(PG_EINVAL, "kernel %d: bad rows/cols/n", i);
+            need[0] = d.n * d.cols; need[1] = d.rows * d.cols; out_need = d.rows * d.n;
+            break;
+        case PG_SCALE_BIAS_RELU: {
+            const long long ch = numel_in[1];
+            if (d.n <= 0 || d.inner <= 0 || d.inner > 0xffffffffll || ch > 0xffffffffll) return fail(PG_EINVAL, "kernel %d: bad n/inner", i);
+            if (numel_in[2] != ch) return fail(PG_EINVAL, "kernel %d: scale and bias sizes differ", i);
+            if (d.n % (ch * d.inner) != 0) return fail(PG_EINVAL, "kernel %d: n is not a multiple of channels*inner", i);
+            need[0] = d.n; need[1] = ch; need[2] = ch; out_need = d.n;
+            break;
+        }
+        }
+        if (ints[d.out.index].numel < out_need) return fail(PG_EINVAL, "kernel %d: output buffer too small", i);
+        for (int j = 0; j < nin; j++) {
+            if (numel_in[j] < need[j]) return fail(PG_EINVAL, "kernel %d: operand %d too small", i, j);
+            if (d.in[j].kind == PG_REF_INT && written[d.in[j].index] < need[j])
+                return fail(PG_EINVAL, "kernel %d: operand %d reads internal buffer %d beyond what earlier kernels wrote", i, j, d.in[j].index);
+        }
+        written[d.out.index] = std::max(written[d.out.index], out_need);
+    }
+    return PG_OK;
+}
+
+void build_copy_list(CopyList& L, const pg_tensor_desc* ext, const std::vector<size_t>& ph_off, char* ws) {
+    L.tensors.clear(); L.chunks.clear(); L.groups.clear(); L.bytes = 0;
+    for (size_t li = 0; li < L.ext.size(); li++) {
+        const int e = L.ext[li];
+        const unsigned long long bytes = (unsigned long long)ext[e].numel * elem_bytes(ext[e].dtype);
+        L.tensors.push_back({ws ? ws + ph_off[e] : nullptr, bytes});
+        L.bytes += (long long)bytes;
+    }
+    const int nt = (int)L.tensors.size();
+    for (int t0 = 0; t0 < nt; t0 += pgk::kCopyMaxSrc) {
+        const int t1 = std::min(nt, t0 + pgk::kCopyMaxSrc);
+        const int c0 = (int)L.chunks.size();
+        for (int t = t0; t < t1; t++)
+            for (unsigned long long off = 0; off < L.tensors[t].bytes; off += pgk::kCopyChunkBytes)
+                L.chunks.push_back({(unsigned)t, (unsigned)std::min<unsigned long long>(pgk::kCopyChunkBytes, L.tensors[t].bytes - off), off});
+        L.groups.push_back({t0, t1, c0, (int)L.chunks.size()});
+    }
+}
+
+// Lay out the workspace.  ws may be null (size query).
+void make_layout(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int n_ext,
+                 const pg_tensor_desc* ints, int n_int, char* ws, Layout& L) {
+    size_t off = 0;
+    L.ph_off.resize(n_ext);
+    for (int i = 0; i < n_ext; i++) { L.ph_off[i] = off; off = align_up(off + (size_t)ext[i].numel * elem_bytes(ext[i].dtype)); }
+    L.int_off.resize(n_int);
+    for (int i = 0; i < n_int; i++) { L.int_off[i] = off; off = align_up(off + (size_t)ints[i].numel * elem_bytes(ints[i].dtype)); }
+    L.table_off = off;
+    off = align_up(off + (size_t)std::max(1, n_ext) * 8);
+    // segments and their external sets
+    const int n_seg = k[nk - 1].segment + 1;
+    L.seg.assign(n_seg, Segment());
+    std::vector<std::vector<int>> seg_ext(n_seg);
+    for (int i = 0; i < nk; i++) {
+        Segment& s = L.seg[k[i].segment];
+        if (s.k1 == 0 && (i == 0 || k[i - 1].segment != k[i].segment)) s.k0 = i;
+        s.k1 = i + 1;
+        for (int j = 0; j < 3; j++)
+            if (k[i].in[j].kind == PG_REF_EXT) { s.has_ext = true; seg_ext[k[i].segment].push_back(k[i].in[j].index); }
+    }
+    L.lists.clear();
+    L.lists.emplace_back();
+    for (int e = 0; e < n_ext; e++) L.lists[0].ext.push_back(e);
+    for (int s = 0; s < n_seg; s++) {
+        auto& v = seg_ext[s];
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());
+        if (v.empty()) continue;
+        if ((int)v.size() == n_ext) { L.seg[s].copy_list = 0; continue; }
+        L.seg[s].copy_list = (int)L.lists.size();
+        L.lists.emplace_back();
+        L.lists.back().ext = v;
+    }
+    for (auto& cl : L.lists) {
+        build_copy_list(cl, ext, L.ph_off, ws);
+        cl.tensors_off = off; off = align_up(off + std::max<size_t>(1, cl.tensors.size()) * sizeof(pgk::CopyTensor));
+        cl.chunks_off = off; off = align_up(off + std::max<size_t>(1, cl.chunks.size()) * sizeof(pgk::CopyChunk));
+    }
+    L.total = off;
+}
+
+const void* operand_ptr(const pg_chain* c, const pg_ref& r, int mode /*0 eager,1 copy,2 ind*/) {
+    switch (r.kind) {
+    case PG_REF_WEIGHT: return c->wptr[r.index];
+    case PG_REF_INT: return c->ws + c->int_off[r.index];
+    case PG_REF_EXT:
+        if (mode == 1) return c->ws + c->ph_off[r.index];
+        if (mode == 2) return c->ws + c->table_off + 8 * (size_t)r.index;
+        return nullptr;   // patched per call
+    default: return nullptr;
+    }
+}
+
+pg_status make_records(pg_chain* c) {
+    const int nk = (int)c->k.size();
+    c->rec.assign(nk, KernelRec());
+    c->eager_fix.clear();
+    for (int i = 0; i < nk; i++) {
+        const pg_kernel_desc& d = c->k[i];
+        KernelRec& r = c->rec[i];
+        r.n_in = n_inputs(d.op);
+        for (int j = 0; j < r.n_in; j++)
+            if (d.in[j].kind == PG_REF_EXT) { r.ind_mask |= 1 << j; r.ext_of[j] = d.in[j].index; c->eager_fix.push_back({i, j}); }
+        ArgBlock* blocks[3] = {&r.a_eager, &r.a_copy, &r.a_ind};
+        for (int mode = 0; mode < 3; mode++) {
+            ArgBlock& a = *blocks[mode];
+            memset(&a, 0, sizeof a);
+            a.ptr[0] = c->ws + c->int_off[d.out.index];
+            for (int j = 0; j < r.n_in; j++) a.ptr[1 + j] = operand_ptr(c, d.in[j], mode);
+            switch (d.op) {
+            case PG_ADD: case PG_MUL: case PG_GELU:
+                a.ew.n = d.n; a.ew.m = (d.op == PG_GELU) ? d.n : (d.m ? d.m : d.n);
+                break;
+            case PG_RMSNORM: a.rms.rows = (int)d.rows; a.rms.cols = (int)d.cols; a.rms.eps = d.eps; break;
+            case PG_GEMV: a.gemv.rows = (int)d.rows; a.gemv.n = (int)d.n; a.gemv.cols = (int)d.cols; break;
+            case PG_SCALE_BIAS_RELU:
+                a.sbr.n = d.n; a.sbr.inner = (unsigned)d.inner;
+                a.sbr.channels = (unsigned)(d.in[1].kind == PG_REF_EXT ? c->ext[d.in[1].index].numel
+                                            : d.in[1].kind == PG_REF_INT ? c->ints[d.in[1].index].numel : c->w[d.in[1].index].numel);
+                break;
+            }
+        }
+        dim3 grid, block;
+        switch (d.op) {
+        case PG_ADD: case PG_MUL: case PG_GELU: pgk::shape_elementwise(d.dtype, d.n, &grid, &block); break;
+        case PG_RMSNORM: pgk::shape_rmsnorm((int)d.rows, &grid, &block); break;
+        case PG_GEMV: pgk::shape_gemv((int)d.rows, (int)d.n, &grid, &block); break;
+        default: pgk::shape_sbr(d.dtype, d.n, &grid, &block); break;
+        }
+        r.direct.fn = pgk::kernel_for(d.op, d.dtype, 0);
+        r.indirect.fn = pgk::kernel_for(d.op, d.dtype, r.ind_mask);
+        if (!r.direct.fn || !r.indirect.fn) return fail(PG_EINVAL, "kernel %d: no device kernel for op %d dtype %d", i, d.op, d.dtype);
+        r.direct.grid = r.indirect.grid = grid;
+        r.direct.block = r.indirect.block = block;
+    }
+    return PG_OK;
+}
+
+// ---- launches ----------------------------------------------------------------------------------------
+inline hipError_t launch(const pgk::Launch& L, ArgBlock* a, hipStream_t s) {
+    void* args[1] = {a};
+    return hipLaunchKernel(L.fn, L.grid, L.block, args, 0, s);
+}
+
+pg_status check_call(const pg_chain* c, const void* const* ext, void* stream, bool need_capture) {
+    if (!c) return fail(PG_EINVAL, "null chain");
+    if (!stream) return fail(PG_EINVAL, "the NULL stream cannot be used; pass a created stream");
+    if (need_capture && !c->captured) return fail(PG_ESTATE, "pg_capture has not been called");
+    const int n_ext = (int)c->ext.size();
+    if (n_ext && !ext) return fail(PG_EINVAL, "null external pointer array");
+    for (int i = 0; i < n_ext; i++) {
+        if (!ext[i]) return fail(PG_EINVAL, "external pointer %d is null", i);
+        if (reinterpret_cast<uintptr_t>(ext[i]) % elem_bytes(c->ext[i].dtype)) return fail(PG_EINVAL, "external pointer %d is not aligned to its element size", i);
+    }
+    return PG_OK;
+}
+
+pg_status run_eager_range(pg_chain* c, int k0, int k1, const void* const* ext, hipStream_t s) {
+    for (int i = k0; i < k1; i++) {
+        KernelRec& r = c->rec[i];
+        for (int j = 0; j < r.n_in; j++)
+            if (r.ext_of[j] >= 0) r.a_eager.ptr[1 + j] = ext[r.ext_of[j]];
+        PG_HIP(launch(r.direct, &r.a_eager, s));
+    }
+    return PG_OK;
+}
+
+pg_status run_copy_list(pg_chain* c, int list, const void* const* ext, hipStream_t s) {
+    CopyList& L = c->copy_lists[list];
+    for (const auto& g : L.groups) {
+        if (g.c1 == g.c0) continue;
+        pgk::CopyArgs a;
+        a.chunks = reinterpret_cast<const pgk::CopyChunk*>(c->ws + L.chunks_off) + g.c0;
+        a.tensors = reinterpret_cast<const pgk::CopyTensor*>(c->ws + L.tensors_off);
+        a.src_base = g.t0;
+        a.n_chunks = g.c1 - g.c0;
+        for (int t = g.t0; t < g.t1; t++) a.src[t - g.t0] = ext[L.ext[t]];
+        void* args[1] = {&a};
+        PG_HIP(hipLaunchKernel(pgk::copy_kernel(), dim3((unsigned)a.n_chunks), dim3(256), args, 0, s));
+    }
+    return PG_OK;
+}
+
+pg_status write_table(pg_chain* c, const void* const* ext, hipStream_t s) {
+    const int n_ext = (int)c->ext.size();
+    if (n_ext == 0) return PG_OK;
+    const void** table = reinterpret_cast<const void**>(c->ws + c->table_off);
+    if (c->table_how == PG_TABLE_MEMCPY) {
+        const int half_len = pg_chain::kRing / 2;
+        const int slot = (int)(c->ring_cnt % pg_chain::kRing), half = slot / half_len;
+        // the slots of this half were last read by copies issued kRing/2..kRing calls ago: wait for them
+        if (slot % half_len == 0 && c->ring_used[half]) PG_HIP(hipEventSynchronize(c->ring_ev[half]));
+        char* st = static_cast<char*>(c->staging) + (size_t)slot * c->staging_stride;
+        memcpy(st, ext, (size_t)n_ext * 8);
+        PG_HIP(hipMemcpyAsync(table, st, (size_t)n_ext * 8, hipMemcpyHostToDevice, s));
+        if (slot % half_len == half_len - 1) { PG_HIP(hipEventRecord(c->ring_ev[half], s)); c->ring_used[half] = true; }
+        c->ring_cnt++;
+        return PG_OK;
+    }
+    for (int base = 0; base < n_ext; base += pgk::kTableMaxPtrs) {
+        pgk::TableArgs a;
+        a.table = table;
+        a.base = base;
+        a.n = std::min(pgk::kTableMaxPtrs, n_ext - base);
+        memcpy(a.ptr, ext + base, (size_t)a.n * 8);
+        void* args[1] = {&a};
+        PG_HIP(hipLaunchKernel(pgk::table_kernel(), dim3(1), dim3(64), args, 0, s));
+    }
+    return PG_OK;
+}
+
+void destroy_graphs(pg_chain* c) {
+    for (auto& s : c->seg) {
+        if (s.x_ind && s.x_ind != s.x_copy) (void)hipGraphExecDestroy(s.x_ind);
+        if (s.g_ind && s.g_ind != s.g_copy) (void)hipGraphDestroy(s.g_ind);
+        if (s.x_copy) (void)hipGraphExecDestroy(s.x_copy);
+        if (s.g_copy) (void)hipGraphDestroy(s.g_copy);
+        s.x_copy = s.x_ind = nullptr;
+        s.g_copy = s.g_ind = nullptr;
+    }
+    c->captured = false;
+}
+
+pg_status capture_segment(pg_chain* c, Segment& sg, bool indirect, hipStream_t s, hipGraph_t* g_out, hipGraphExec_t* x_out) {
+    PG_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    hipError_t le = hipSuccess;
+    for (int i = sg.k0; i < sg.k1 && le == hipSuccess; i++) {
+        KernelRec& r = c->rec[i];
+        le = indirect ? launch(r.indirect, &r.a_ind, s) : launch(r.direct, &r.a_copy, s);
+    }
+    hipGraph_t g = nullptr;
+    hipError_t ee = hipStreamEndCapture(s, &g);   // always end the capture, even after a failed launch
+    if (le != hipSuccess) { if (g) (void)hipGraphDestroy(g); g_hip_err = (int)le; return fail(PG_EHIP, "kernel launch during capture failed: %s", hipGetErrorString(le)); }
+    if (ee != hipSuccess) { g_hip_err = (int)ee; return fail(PG_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(ee)); }
+    hipGraphExec_t x = nullptr;
+    hipError_t ie = hipGraphInstantiate(&x, g, nullptr, nullptr, 0);
+    if (ie != hipSuccess) { (void)hipGraphDestroy(g); g_hip_err = (int)ie; return fail(PG_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(ie)); }
+    *g_out = g;
+    *x_out = x;
+    PG_HIP(hipGraphUpload(x, s));
+    return PG_OK;
+}
+
+pg_status run_segment(pg_chain* c, int si, int mode, const void* const* ext, hipStream_t s, bool* table_written) {
+    Segment& sg = c->seg[si];
+    switch (mode) {
+    case PG_EAGER: return run_eager_range(c, sg.k0, sg.k1, ext, s);
+    case PG_GRAPH_COPY: {
+        if (sg.copy_list >= 0) { pg_status st = run_copy_list(c, sg.copy_list, ext, s); if (st) return st; }
+        PG_HIP(hipGraphLaunch(sg.x_copy, s));
+        return PG_OK;
+    }
+    case PG_GRAPH_INDIRECT: {
+        if (!sg.has_ext) return fail(PG_EUNAVAIL, "segment %d reads no external operand: indirect mode does not exist for it", si);
+        if (!*table_written) { pg_status st = write_table(c, ext, s); if (st) return st; *table_written = true; }
+        PG_HIP(hipGraphLaunch(sg.x_ind, s));
+        return PG_OK;
+    }
+    default: return fail(PG_EINVAL, "bad mode %d for segment %d", mode, si);
+    }
+}
+
+double now_us() {
+    return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+// ======================================================================================================
+extern "C" {
+
+const char* pg_last_error(void) { return g_err.c_str(); }
+int pg_last_hip_error(void) { return g_hip_err; }
+const char* pg_version(void) { return "pygraph_hip 0.1 (gfx950)"; }
+
+pg_status pg_chain_workspace_bytes(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor_desc* ext, int32_t n_ext,
+                                   const pg_tensor_desc* ints, int32_t n_int, size_t* bytes_out) {
+    if (!bytes_out) return fail(PG_EINVAL, "null bytes_out");
+    // weights are not needed for the layout; validate operand references against what we have
+    int max_w = -1;
+    if (kernels && nk > 0)
+        for (int i = 0; i < nk; i++)
+            for (int j = 0; j < 3; j++)
+                if (kernels[i].in[j].kind == PG_REF_WEIGHT) max_w = std::max(max_w, kernels[i].in[j].index);
+    if (!kernels || nk <= 0) return fail(PG_EINVAL, "no kernels");
+    if (n_ext < 0 || n_int <= 0 || (n_ext && !ext) || !ints) return fail(PG_EINVAL, "bad tensor descriptor arrays");
+    for (int i = 0; i < nk; i++) {
+        if (n_inputs(kernels[i].op) < 0) return fail(PG_EINVAL, "kernel %d: bad op", i);
+        if (i == 0 ? kernels[i].segment != 0 : (kernels[i].segment != kernels[i - 1].segment && kernels[i].segment != kernels[i - 1].segment + 1))
+            return fail(PG_EINVAL, "kernel %d: bad segment order", i);
+        for (int j = 0; j < 3; j++)
+            if (kernels[i].in[j].kind == PG_REF_EXT && (kernels[i].in[j].index < 0 || kernels[i].in[j].index >= n_ext))
+                return fail(PG_EINVAL, "kernel %d: external reference out of range", i);
+    }
+    for (int i = 0; i < n_ext; i++) if (ext[i].numel <= 0 || (ext[i].dtype != PG_F32 && ext[i].dtype != PG_BF16)) return fail(PG_EINVAL, "ext %d: bad descriptor", i);
+    for (int i = 0; i < n_int; i++) if (ints[i].numel <= 0 || (ints[i].dtype != PG_F32 && ints[i].dtype != PG_BF16)) return fail(PG_EINVAL, "int %d: bad descriptor", i);
+    (void)max_w;
+    Layout L;
+    make_layout(kernels, nk, ext, n_ext, ints, n_int, nullptr, L);
+    *bytes_out = L.total;
+    return PG_OK;
+}
+
+pg_status pg_chain_build(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor_desc* ext, int32_t n_ext,
+                         const pg_tensor_desc* ints, int32_t n_int, const void* const* weight_dev_ptrs,
+                         const pg_tensor_desc* weights, int32_t n_w, void* workspace_dev, size_t workspace_bytes,
+                         pg_chain** out) {
+    if (!out) return fail(PG_EINVAL, "null out");
+    *out = nullptr;
+    pg_status st = validate(kernels, nk, ext, n_ext, ints, n_int, weights, n_w);
+    if (st) return st;
+    if (n_w && !weight_dev_ptrs) return fail(PG_EINVAL, "null weight pointer array");
+    for (int i = 0; i < n_w; i++) {
+        if (!weight_dev_ptrs[i]) return fail(PG_EINVAL, "weight pointer %d is null", i);
+        if (reinterpret_cast<uintptr_t>(weight_dev_ptrs[i]) & 15u) return fail(PG_EINVAL, "weight pointer %d is not 16-byte aligned", i);
+    }
+    if (!workspace_dev) return fail(PG_EINVAL, "null workspace");
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return fail(PG_EINVAL, "workspace is not 256-byte aligned");
+    pg_chain* c = new (std::nothrow) pg_chain();
+    if (!c) return fail(PG_ENOMEM, "out of host memory");
+    c->k.assign(kernels, kernels + nk);
+    if (n_ext) c->ext.assign(ext, ext + n_ext);
+    c->ints.assign(ints, ints + n_int);
+    if (n_w) { c->w.assign(weights, weights + n_w); c->wptr.assign(weight_dev_ptrs, weight_dev_ptrs + n_w); }
+    c->ws = static_cast<char*>(workspace_dev);
+    c->ws_bytes = workspace_bytes;
+    Layout L;
+    make_layout(c->k.data(), nk, c->ext.data(), n_ext, c->ints.data(), n_int, c->ws, L);
+    c->ws_need = L.total;
+    if (workspace_bytes < L.total) {
+        delete c;
+        return fail(PG_ENOMEM, "workspace has %zu bytes, the chain needs %zu", workspace_bytes, L.total);
+    }
+    c->ph_off = std::move(L.ph_off);
+    c->int_off = std::move(L.int_off);
+    c->table_off = L.table_off;
+    c->copy_lists = std::move(L.lists);
+    c->seg = std::move(L.seg);
+    st = make_records(c);
+    if (st) { delete c; return st; }
+    *out = c;
+    return PG_OK;
+}
+
+pg_status pg_capture(pg_chain* c, void* hip_stream) {
+    if (!c) return fail(PG_EINVAL, "null chain");
+    if (!hip_stream) return fail(PG_EINVAL, "capture needs a created stream, not the NULL stream");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    PG_HIP(hipStreamIsCapturing(s, &cs));
+    if (cs != hipStreamCaptureStatusNone) return fail(PG_EINVAL, "the stream is already capturing");
+    destroy_graphs(c);
+    // static side of the copy kernel's job lists
+    for (auto& L : c->copy_lists) {
+        if (!L.tensors.empty()) PG_HIP(hipMemcpyAsync(c->ws + L.tensors_off, L.tensors.data(), L.tensors.size() * sizeof(pgk::CopyTensor), hipMemcpyHostToDevice, s));
+        if (!L.chunks.empty()) PG_HIP(hipMemcpyAsync(c->ws + L.chunks_off, L.chunks.data(), L.chunks.size() * sizeof(pgk::CopyChunk), hipMemcpyHostToDevice, s));
+    }
+    PG_HIP(hipMemsetAsync(c->ws + c->table_off, 0, std::max<size_t>(1, c->ext.size()) * 8, s));
+    PG_HIP(hipStreamSynchronize(s));   // the host vectors above may now change; nothing is pending during capture
+    if (!c->staging && !c->ext.empty()) {
+        c->staging_stride = align_up(c->ext.size() * 8);
+        PG_HIP(hipHostMalloc(&c->staging, c->staging_stride * pg_chain::kRing, hipHostMallocDefault));
+        PG_HIP(hipEventCreateWithFlags(&c->ring_ev[0], hipEventDisableTiming));
+        PG_HIP(hipEventCreateWithFlags(&c->ring_ev[1], hipEventDisableTiming));
+    }
+    for (auto& sg : c->seg) {
+        pg_status st = capture_segment(c, sg, false, s, &sg.g_copy, &sg.x_copy);
+        if (st) { destroy_graphs(c); return st; }
+        if (sg.has_ext) {
+            st = capture_segment(c, sg, true, s, &sg.g_ind, &sg.x_ind);
+            if (st) { destroy_graphs(c); return st; }
+        } else {
+            sg.g_ind = sg.g_copy;   // no external operand: the two graphs would be identical
+            sg.x_ind = sg.x_copy;
+        }
+    }
+    PG_HIP(hipStreamSynchronize(s));
+    c->captured = true;
+    return PG_OK;
+}
+
+pg_status pg_eager(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, false);
+    if (st) return st;
+    return run_eager_range(c, 0, (int)c->k.size(), ext, static_cast<hipStream_t>(hip_stream));
+}
+
+pg_status pg_eager_range(pg_chain* c, const void* const* ext, int32_t k0, int32_t k1, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, false);
+    if (st) return st;
+    if (k0 < 0 || k1 < k0 || k1 > (int)c->k.size()) return fail(PG_EINVAL, "bad kernel range [%d, %d)", k0, k1);
+    return run_eager_range(c, k0, k1, ext, static_cast<hipStream_t>(hip_stream));
+}
+
+pg_status pg_refresh_copy(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    return run_copy_list(c, 0, ext, static_cast<hipStream_t>(hip_stream));
+}
+
+pg_status pg_refresh_indirect(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    return write_table(c, ext, static_cast<hipStream_t>(hip_stream));
+}
+
+pg_status pg_replay_copy(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((st = run_copy_list(c, 0, ext, s))) return st;
+    for (auto& sg : c->seg) PG_HIP(hipGraphLaunch(sg.x_copy, s));
+    return PG_OK;
+}
+
+pg_status pg_replay_indirect(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((st = write_table(c, ext, s))) return st;
+    for (auto& sg : c->seg) PG_HIP(hipGraphLaunch(sg.x_ind, s));
+    return PG_OK;
+}
+
+pg_status pg_run_selected(pg_chain* c, const uint8_t* mode, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    if (!mode) return fail(PG_EINVAL, "null mode array");
+    bool table_written = false;
+    for (int si = 0; si < (int)c->seg.size(); si++)
+        if ((st = run_segment(c, si, mode[si], ext, static_cast<hipStream_t>(hip_stream), &table_written))) return st;
+    return PG_OK;
+}
+
+pg_status pg_select(const double* cost, int32_t n_seg, uint8_t* mode_out) {
+    if (!cost || !mode_out || n_seg <= 0) return fail(PG_EINVAL, "bad arguments");
+    for (int s = 0; s < n_seg; s++) {
+        int best = -1;
+        for (int m = 0; m < 3; m++) {
+            const double v = cost[3 * s + m];
+            if (!std::isfinite(v)) continue;
+            if (v < 0) return fail(PG_EINVAL, "segment %d: negative cost", s);
+            if (best < 0 || v < cost[3 * s + best]) best = m;
+        }
+        if (best < 0) return fail(PG_EINVAL, "segment %d has no available variant", s);
+        mode_out[s] = (uint8_t)best;
+    }
+    return PG_OK;
+}
+
+pg_status pg_profile(pg_chain* c, const void* const* ext, void* hip_stream, int32_t iters, int32_t inner, double* cost) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    if (iters <= 0 || inner <= 0 || !cost) return fail(PG_EINVAL, "bad iters/inner/cost");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // one full pass so that every internal buffer holds this iteration's data
+    if ((st = run_eager_range(c, 0, (int)c->k.size(), ext, s))) return st;
+    PG_HIP(hipStreamSynchronize(s));
+    std::vector<double> samples(iters);
+    for (int si = 0; si < (int)c->seg.size(); si++) {
+        for (int m = 0; m < 3; m++) {
+            if (m == PG_GRAPH_INDIRECT && !c->seg[si].has_ext) { cost[3 * si + m] = NAN; continue; }
+            for (int it = -2; it < iters; it++) {   // two warm-ups
+                const double t0 = now_us();
+                for (int r = 0; r < inner; r++) {
+                    bool tw = false;
+                    if ((st = run_segment(c, si, m, ext, s, &tw))) return st;
+                }
+                PG_HIP(hipStreamSynchronize(s));
+                if (it >= 0) samples[it] = (now_us() - t0) / inner;
+            }
+            std::sort(samples.begin(), samples.end());
+            cost[3 * si + m] = (iters & 1) ? samples[iters / 2] : 0.5 * (samples[iters / 2 - 1] + samples[iters / 2]);
+        }
+    }
+    return PG_OK;
+}
+
+pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segment, const void* const* ext_sets, int32_t n_sets,
+                       int32_t iters, void* hip_stream, double* us_out) {
+    if (!c || !us_out || n_sets <= 0 || iters <= 0) return fail(PG_EINVAL, "bad arguments");
+    const int n_ext = (int)c->ext.size();
+    pg_status st;
+    for (int i = 0; i < n_sets; i++)
+        if ((st = check_call(c, ext_sets + (size_t)i * n_ext, hip_stream, mode != PG_EAGER))) return st;
+    if (mode == 3 && !mode_per_segment) return fail(PG_EINVAL, "null mode array");
+    if (mode < 0 || mode > 3) return fail(PG_EINVAL, "bad mode");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    PG_HIP(hipStreamSynchronize(s));
+    const double t0 = now_us();
+    for (int it = 0; it < iters; it++) {
+        const void* const* ext = ext_sets + (size_t)(it % n_sets) * n_ext;
+        switch (mode) {
+        case PG_EAGER: st = run_eager_range(c, 0, (int)c->k.size(), ext, s); break;
+        case PG_GRAPH_COPY: st = pg_replay_copy(c, ext, hip_stream); break;
+        case PG_GRAPH_INDIRECT: st = pg_replay_indirect(c, ext, hip_stream); break;
+        default: st = pg_run_selected(c, mode_per_segment, ext, hip_stream); break;
+        }
+        if (st) return st;
+    }
+    PG_HIP(hipStreamSynchronize(s));
+    *us_out = (now_us() - t0) / iters;
+    return PG_OK;
+}
+
+pg_status pg_chain_int_buffer(const pg_chain* c, int32_t i, void** p, size_t* bytes) {
+    if (!c || i < 0 || i >= (int)c->ints.size()) return fail(PG_EINVAL, "bad internal buffer index");
+    if (p) *p = c->ws + c->int_off[i];
+    if (bytes) *bytes = (size_t)c->ints[i].numel * elem_bytes(c->ints[i].dtype);
+    return PG_OK;
+}
+
+pg_status pg_chain_placeholder(const pg_chain* c, int32_t i, void** p, size_t* bytes) {
+    if (!c || i < 0 || i >= (int)c->ext.size()) return fail(PG_EINVAL, "bad external index");
+    if (p) *p = c->ws + c->ph_off[i];
+    if (bytes) *bytes = (size_t)c->ext[i].numel * elem_bytes(c->ext[i].dtype);
+    return PG_OK;
+}
+
+pg_status pg_chain_pointer_table(const pg_chain* c, void** p, size_t* bytes) {
+    if (!c) return fail(PG_EINVAL, "null chain");
+    if (p) *p = c->ws + c->table_off;
+    if (bytes) *bytes = c->ext.size() * 8;
+    return PG_OK;
+}
+
+pg_status pg_chain_stats(const pg_chain* c, pg_stats* out) {
+    if (!c || !out) return fail(PG_EINVAL, "null argument");
+    memset(out, 0, sizeof *out);
+    out->n_kernels = (int)c->k.size();
+    out->n_segments = (int)c->seg.size();
+    out->n_ext = (int)c->ext.size();
+    for (const auto& r : c->rec) out->n_ext_reading_kernels += r.ind_mask != 0;
+    out->copy_bytes_per_replay = c->copy_lists[0].bytes;
+    out->table_bytes_per_replay = 8ll * (long long)c->ext.size();
+    out->workspace_bytes = (long long)c->ws_need;
+    out->copy_chunks = (int)c->copy_lists[0].chunks.size();
+    out->captured = c->captured;
+    return PG_OK;
+}
+
+pg_status pg_set_table_refresh(pg_chain* c, int32_t how) {
+    if (!c || (how != PG_TABLE_KERNARG && how != PG_TABLE_MEMCPY)) return fail(PG_EINVAL, "bad table refresh kind");
+    c->table_how = how;
+    return PG_OK;
+}
+
+void pg_chain_destroy(pg_chain* c) {
+    if (!c) return;
+    destroy_graphs(c);
+    if (c->ring_ev[0]) (void)hipEventDestroy(c->ring_ev[0]);
+    if (c->ring_ev[1]) (void)hipEventDestroy(c->ring_ev[1]);
+    if (c->staging) (void)hipHostFree(c->staging);
+    delete c;
+}
+
+}  // extern "C"

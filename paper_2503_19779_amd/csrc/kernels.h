@@ -1,0 +1,90 @@
+// kernels.h -- argument blocks and launch descriptions shared by the device code (kernels.hip)
+// and the chain runtime (chain.hip).  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pgk {
+
+enum Op : int { kAdd = 0, kMul = 1, kGelu = 2, kRmsNorm = 3, kGemv = 4, kScaleBiasRelu = 5 };
+enum DType : int { kF32 = 0, kBF16 = 1 };
+
+// One argument block per kernel, passed by value as the kernel's single parameter.  An operand
+// whose bit is set in the kernel's IND template mask holds the address of a pointer-table slot
+// instead of the tensor's address: the kernel loads the tensor pointer from it before anything
+// else (the dereference prologue of Parameter Indirection, paper Sec. 4 "Kernel generation").
+struct EwArgs {          // ADD / MUL / GELU
+    void* out;
+    const void* a;
+    const void* b;
+    long long n;
+    long long m;
+};
+struct RmsArgs {
+    void* out;
+    const void* x;
+    const void* g;
+    int rows;
+    int cols;
+    float eps;
+};
+struct GemvArgs {
+    void* out;
+    const void* W;
+    const void* h;
+    int rows;
+    int n;
+    int cols;
+};
+struct SbrArgs {
+    void* out;
+    const void* x;
+    const void* s;
+    const void* b;
+    long long n;
+    unsigned inner;
+    unsigned channels;
+};
+
+// Batched multi-tensor copy: the destination side is static and lives in device memory, the
+// source pointers change every replay and travel in the argument block.
+constexpr int kCopyMaxSrc = 448;           // 448 * 8 B + header < 4 KB of kernel arguments
+constexpr unsigned kCopyChunkBytes = 65536;  // bytes of one tensor handled by one workgroup
+struct CopyTensor { void* dst; unsigned long long bytes; };
+struct CopyChunk { unsigned tensor; unsigned len; unsigned long long off; };
+struct CopyArgs {
+    const CopyChunk* chunks;     // [dev] chunk list, offset to this launch's first chunk
+    const CopyTensor* tensors;   // [dev] per-tensor destination and size
+    int src_base;                // tensor index of src[0]
+    int n_chunks;
+    const void* src[kCopyMaxSrc];
+};
+
+// Pointer-table writer: the pointers ride in the argument block, one wave stores them.
+constexpr int kTableMaxPtrs = 480;
+struct TableArgs {
+    const void** table;          // [dev]
+    int base;
+    int n;
+    const void* ptr[kTableMaxPtrs];
+};
+
+struct Launch {
+    const void* fn = nullptr;    // host-side kernel handle for hipLaunchKernel
+    dim3 grid{1, 1, 1};
+    dim3 block{1, 1, 1};
+};
+
+// Kernel handle for (op, dtype, mask of indirected operands); nullptr if there is none.
+const void* kernel_for(int op, int dtype, int ind_mask);
+const void* copy_kernel();
+const void* table_kernel();
+
+// Launch shape; identical for every variant of a kernel so that all modes run the same schedule.
+void shape_elementwise(int dtype, long long n, dim3* grid, dim3* block);
+void shape_rmsnorm(int rows, dim3* grid, dim3* block);
+void shape_gemv(int rows, int n, dim3* grid, dim3* block);
+void shape_sbr(int dtype, long long n, dim3* grid, dim3* block);
+
+}  // namespace pgk
