@@ -97,14 +97,21 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // ---- elementwise ----------------------------------------------------------------------------
-template <int OP>
+// GELU(a) = a * Phi(a) with Phi(a) = erfc(-a / sqrt 2) / 2 (keeps relative accuracy in the left
+// tail).  For fp32 tensors it is evaluated in fp64 and rounded once, so that the result is the
+// correctly rounded one except within ~1e-16 of a rounding boundary: an fp32 erfc is a few ulp off,
+// and a chain of multiplies and cancelling adds amplifies that beyond 1e-5.  For bf16 tensors fp32
+// is far more than the 8 stored bits need.
+template <int OP, bool WIDE>
 __device__ __forceinline__ float ew_apply(float a, float b) {
     if constexpr (OP == kAdd) {
         return a + b;
     } else if constexpr (OP == kMul) {
         return a * b;
+    } else if constexpr (WIDE) {
+        const double x = (double)a;
+        return (float)((0.5 * x) * erfc(x * -0.70710678118654752440));
     } else {
-        // a * Phi(a) with Phi(a) = erfc(-a / sqrt 2) / 2: keeps relative accuracy in the left tail
         return (0.5f * a) * erfcf(a * -0.70710678118654752440f);
     }
 }
@@ -137,7 +144,7 @@ __device__ __forceinline__ void ew_body(const T* a, const T* __restrict__ b, T* 
                 Fmt<T>::unpack(ra[u], fa);
                 if constexpr (kBinary) Fmt<T>::unpack(rb[u], fb);
 #pragma unroll
-                for (int e = 0; e < N; e++) fo[e] = ew_apply<OP>(fa[e], kBinary ? fb[e] : 0.f);
+                for (int e = 0; e < N; e++) fo[e] = ew_apply<OP, sizeof(T) == 4>(fa[e], kBinary ? fb[e] : 0.f);
                 st16(o + v * N, Fmt<T>::pack(fo));
             }
         }
@@ -145,7 +152,7 @@ __device__ __forceinline__ void ew_body(const T* a, const T* __restrict__ b, T* 
             const IdxT i = nvec * N + threadIdx.x;
             if (i < n) {
                 const float fb1 = kBinary ? Fmt<T>::load(b + (i % m)) : 0.f;
-                Fmt<T>::store(o + i, ew_apply<OP>(Fmt<T>::load(a + i), fb1));
+                Fmt<T>::store(o + i, ew_apply<OP, sizeof(T) == 4>(Fmt<T>::load(a + i), fb1));
             }
         }
     } else {
@@ -154,7 +161,7 @@ __device__ __forceinline__ void ew_body(const T* a, const T* __restrict__ b, T* 
         const IdxT end = (n - start < tile) ? n : start + tile;
         for (IdxT i = start + threadIdx.x; i < end; i += kBlock) {
             const float fb1 = kBinary ? Fmt<T>::load(b + (i % m)) : 0.f;
-            Fmt<T>::store(o + i, ew_apply<OP>(Fmt<T>::load(a + i), fb1));
+            Fmt<T>::store(o + i, ew_apply<OP, sizeof(T) == 4>(Fmt<T>::load(a + i), fb1));
         }
     }
 }

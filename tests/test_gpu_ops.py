@@ -1,0 +1,219 @@
+"""GPU parity, one kernel at a time: every op through the C ABI in all three modes against the
+CPU oracle, at sizes that span several tiles and a ragged tail, with aligned and misaligned
+operands; and the batched copy kernel against a byte compare."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_19779_amd as pg
+from gpu_util import Harness, assert_close, same_bits, say, as_f64
+from paper_2503_19779_amd.binding import to_device, to_numpy
+from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, EXT, INT, WEIGHT, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+NP = {"f32": np.float32, "bf16": np.uint16}
+EB = {"f32": 4, "bf16": 2}
+
+
+def draw(rng, n, dtype, scale=1.0, mean=0.0):
+    x = (rng.standard_normal(n) * scale + mean).astype(np.float32)
+    return f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+def run_single(spec, ext_np, w_np, offsets=None, what=""):
+    """One-kernel chain: all modes agree bit for bit; returns the output (numpy)."""
+    h = Harness(spec, weights_np=w_np)
+    offsets = offsets or [0] * len(ext_np)
+    holders, ptrs = [], []
+    for x, off in zip(ext_np, offsets):
+        # place the tensor `off` bytes into a larger allocation to control its alignment
+        raw = torch.empty(x.nbytes + 64, dtype=torch.uint8, device="cuda:0")
+        raw[off:off + x.nbytes].copy_(torch.from_numpy(x.view(np.uint8)))
+        holders.append(raw)
+        ptrs.append(raw.data_ptr() + off)
+    outs = {}
+    for mode in ("eager", "copy", "indirect"):
+        h.scrub()
+        outs[mode] = h.run(mode, ptrs)[0]
+    assert same_bits(outs["eager"], outs["copy"]), what + ": eager vs graph-copy"
+    assert same_bits(outs["eager"], outs["indirect"]), what + ": eager vs graph-indirect"
+    h.close()
+    return outs["eager"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("op", ["add", "mul", "gelu"])
+@pytest.mark.parametrize("n,m,offs", [(1, 0, (0, 0)), (7, 0, (0, 0)), (4096, 0, (0, 0)), (4099, 0, (0, 0)),
+                                       (300001, 0, (0, 0)), (9000, 8, (0, 0)), (9001, 24, (0, 0)), (5000, 7, (0, 0)),
+                                       (4099, 0, (4, 0)), (4100, 0, (0, 8)), (70000, 512, (0, 0))])
+def test_elementwise(op, dtype, n, m, offs):
+    rng = np.random.Generator(np.random.PCG64(100 + n))
+    say(f"elementwise {op} {dtype} n={n} m={m} offs={offs}")
+    a = draw(rng, n, dtype, 2.0)
+    nb = m or n
+    b = draw(rng, nb, dtype)
+    if op == "gelu":
+        k = KernelSpec("gelu", dtype, 0, (Ref(EXT, 0),), n)
+        ext, xs, of = [TensorSpec(dtype, n)], [a], [offs[0]]
+    else:
+        k = KernelSpec(op, dtype, 0, (Ref(EXT, 0), Ref(EXT, 1)), n, m=m)
+        ext, xs, of = [TensorSpec(dtype, n), TensorSpec(dtype, nb)], [a, b], list(offs)
+    spec = ChainSpec("one", [k], ext, [TensorSpec(dtype, n)], [], [0])
+    got = run_single(spec, xs, [], of, f"{op} {dtype} n={n}")
+    want = oracle.run_chain(spec, [], xs)[0]
+    if op != "gelu" and dtype == "f32":
+        assert same_bits(got, want)            # + and x are single IEEE operations
+    if op != "gelu" and dtype == "bf16":
+        assert same_bits(got, want)            # exact in fp32, then one rounding: must agree exactly
+    assert_close(got, want, dtype, f"{op} {dtype} n={n}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gelu_special_values(dtype):
+    vals = np.array([0.0, -0.0, 10.0, 12.5, 40.0, 1000.0, -40.0, -100.0, -1e4, 1.0, -1.0, -0.75, 5.0, -5.0, -8.0, 3e-20], np.float32)
+    a = f32_to_bf16_bits(vals) if dtype == "bf16" else vals
+    n = a.size
+    spec = ChainSpec("g", [KernelSpec("gelu", dtype, 0, (Ref(EXT, 0),), n)], [TensorSpec(dtype, n)], [TensorSpec(dtype, n)], [], [0])
+    got = as_f64(run_single(spec, [a], []))
+    x = as_f64(a)
+    assert got[0] == 0 and got[1] == 0
+    assert np.array_equal(got[2:6], x[2:6])                 # identity for large x
+    assert np.all(got[6:9] == 0)                            # zero for very negative x
+    want = as_f64(oracle.run_chain(spec, [], [a])[0])
+    rel = 2e-6 if dtype == "f32" else 2.0 ** -8
+    assert np.all(np.abs(got - want) <= rel * np.abs(want) + 1e-37)   # pure relative, the left tail included
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols,off", [(1, 8, 0), (3, 100, 0), (1, 2048, 0), (5, 2048, 0), (2, 8200, 0), (2, 9000, 0),
+                                            (1, 2048, 4), (3, 37, 0)])
+def test_rmsnorm(dtype, rows, cols, off):
+    if dtype == "bf16" and off % 2:
+        pytest.skip("offset not element aligned")
+    say(f"rmsnorm {dtype} rows={rows} cols={cols} off={off}")
+    rng = np.random.Generator(np.random.PCG64(200 + cols))
+    x = draw(rng, rows * cols, dtype, 3.0)
+    g = draw(rng, cols, dtype, 0.02, 1.0)
+    k = KernelSpec("rmsnorm", dtype, 0, (Ref(EXT, 0), Ref(WEIGHT, 0)), cols, rows=rows, cols=cols, eps=1e-6)
+    spec = ChainSpec("r", [k], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, cols)], [0])
+    got = run_single(spec, [x], [g], [off], "rmsnorm")
+    want = oracle.run_chain(spec, [g], [x])[0]
+    assert_close(got, want, dtype, "rmsnorm", rtol=(1e-5 if dtype == "f32" else 2.0 ** -7))
+    # closed form: constant vector, unit gain
+    c = np.full(rows * cols, 3.0, np.float32)
+    ones = np.ones(cols, np.float32)
+    if dtype == "bf16":
+        c, ones = f32_to_bf16_bits(c), f32_to_bf16_bits(ones)
+    got = as_f64(run_single(spec, [c], [ones], [0], "rmsnorm const"))
+    assert np.allclose(got, 3.0 / np.sqrt(9.0 + 1e-6), rtol=(1e-6 if dtype == "f32" else 2.0 ** -8))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,n,cols", [(1, 5, 24), (1, 2048, 2048), (5, 33, 520), (3, 7, 13), (9, 64, 4096), (1, 130, 2056)])
+def test_gemv(dtype, rows, n, cols):
+    say(f"gemv {dtype} rows={rows} n={n} cols={cols}")
+    rng = np.random.Generator(np.random.PCG64(300 + cols + n))
+    W = draw(rng, n * cols, dtype, 0.02)
+    hh = draw(rng, rows * cols, dtype)
+    k = KernelSpec("gemv", dtype, 0, (Ref(WEIGHT, 0), Ref(EXT, 0)), n, rows=rows, cols=cols)
+    spec = ChainSpec("g", [k], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, rows * n)], [TensorSpec(dtype, n * cols)], [0])
+    got = run_single(spec, [hh], [W], None, "gemv")
+    want = oracle.run_chain(spec, [W], [hh])[0]
+    assert_close(got, want, dtype, "gemv", rtol=(1e-5 if dtype == "f32" else 2.0 ** -7))
+    # integer-valued operands: every partial sum is exact in fp32, so the bits must match any summation order
+    Wi = rng.integers(-2, 3, n * cols).astype(np.float32)
+    hi = rng.integers(-4, 5, rows * cols).astype(np.float32)
+    if dtype == "bf16":
+        Wi, hi = f32_to_bf16_bits(Wi), f32_to_bf16_bits(hi)
+    got = run_single(spec, [hi], [Wi], None, "gemv int")
+    assert same_bits(got, oracle.run_chain(spec, [Wi], [hi])[0])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,C,inner,off", [(2, 3, 5, 0), (2, 8, 900, 0), (3, 4, 49, 0), (1, 64, 12544, 0), (2, 8, 900, 8)])
+def test_scale_bias_relu(dtype, N, C, inner, off):
+    say(f"sbr {dtype} {N}x{C}x{inner} off={off}")
+    rng = np.random.Generator(np.random.PCG64(400 + inner))
+    n = N * C * inner
+    x = draw(rng, n, dtype)
+    s = draw(rng, C, dtype, 0.1, 1.0)
+    b = draw(rng, C, dtype, 0.1)
+    k = KernelSpec("scale_bias_relu", dtype, 0, (Ref(EXT, 0), Ref(WEIGHT, 0), Ref(WEIGHT, 1)), n, inner=inner, channels=C)
+    spec = ChainSpec("s", [k], [TensorSpec(dtype, n)], [TensorSpec(dtype, n)], [TensorSpec(dtype, C), TensorSpec(dtype, C)], [0])
+    got = run_single(spec, [x], [s, b], [off], "sbr")
+    want = oracle.run_chain(spec, [s, b], [x])[0]
+    # fused multiply-add, one rounding: equals the oracle except at double-rounding ties
+    assert np.count_nonzero(got != want) <= max(1, n // 100000)
+    assert_close(got, want, dtype, "sbr")
+
+
+def test_scale_bias_relu_with_external_scale_and_bias():
+    # every operand external: exercises the three-slot indirect variant
+    rng = np.random.Generator(np.random.PCG64(17))
+    N, C, inner = 2, 4, 36
+    n = N * C * inner
+    x, s, b = draw(rng, n, "f32"), draw(rng, C, "f32", 0.1, 1.0), draw(rng, C, "f32", 0.1)
+    k = KernelSpec("scale_bias_relu", "f32", 0, (Ref(EXT, 0), Ref(EXT, 1), Ref(EXT, 2)), n, inner=inner, channels=C)
+    spec = ChainSpec("s", [k], [TensorSpec("f32", n), TensorSpec("f32", C), TensorSpec("f32", C)], [TensorSpec("f32", n)], [], [0])
+    got = run_single(spec, [x, s, b], [], None, "sbr ext")
+    assert_close(got, oracle.run_chain(spec, [], [x, s, b])[0], "f32", "sbr ext")
+
+
+# ------------------------------------------------------------------ the batched copy kernel
+def test_copy_kernel_sizes_and_misalignments():
+    """Placeholder == source, byte for byte, for sizes around every boundary of the kernel (vector
+    width, chunk size) and every element-aligned source misalignment."""
+    sizes = [2, 4, 14, 16, 18, 30, 1022, 1024, 1026, 65534, 65536, 65538, 131072 + 6, 16 * 2 ** 20, 16 * 2 ** 20 + 2]
+    ext = [TensorSpec("bf16", s // 2) for s in sizes]
+    # one kernel that reads the first external so that the chain is valid; the copy list covers all of them
+    ks = [KernelSpec("gelu", "bf16", 0, (Ref(EXT, 0),), 1)]
+    spec = ChainSpec("copy", ks, ext, [TensorSpec("bf16", 1)], [], [0])
+    h = Harness(spec)
+    rng = np.random.Generator(np.random.PCG64(9))
+    for mis in (0, 2, 4, 6, 8, 10, 12, 14):
+        say(f"copy kernel misalignment {mis}")
+        holders, ptrs, srcs = [], [], []
+        for s in sizes:
+            data = rng.integers(0, 256, s, dtype=np.uint8)
+            raw = torch.empty(s + 64, dtype=torch.uint8, device="cuda:0")
+            raw[mis:mis + s].copy_(torch.from_numpy(data))
+            holders.append(raw); ptrs.append(raw.data_ptr() + mis); srcs.append(data)
+        h.scrub()
+        guard = [h.chain.workspace.clone()]
+        h.chain.refresh_copy(ptrs, h.stream)
+        h.stream.synchronize()
+        for i, data in enumerate(srcs):
+            got = h.chain.placeholder(i).view(torch.uint8).cpu().numpy()
+            assert got.size == data.size and np.array_equal(got, data), f"tensor {i} size {sizes[i]} misalignment {mis}"
+        # nothing outside the placeholders was written
+        after = h.chain.workspace.cpu().numpy()
+        before = guard[0].cpu().numpy()
+        mask = np.ones(after.size, bool)
+        for i in range(len(sizes)):
+            off, nb = h.chain.raw_layout("ext", i)
+            mask[off:off + nb] = False
+        assert np.array_equal(after[mask], before[mask])
+    st = h.chain.stats()
+    assert st["copy_bytes_per_replay"] == sum(sizes)
+    h.close()
+
+
+def test_copy_kernel_many_tensors_in_groups():
+    """More tensors than one launch's argument block carries (two launches)."""
+    n_t = 600
+    ext = [TensorSpec("f32", 3 + (i % 7)) for i in range(n_t)]
+    ks = [KernelSpec("gelu", "f32", 0, (Ref(EXT, n_t - 1),), 3)]
+    spec = ChainSpec("copy", ks, ext, [TensorSpec("f32", 4)], [], [0])
+    h = Harness(spec)
+    x_np, x_dev = h.inputs(0)
+    h.scrub()
+    h.chain.refresh_copy(x_dev, h.stream)
+    h.chain.refresh_indirect(x_dev, h.stream)
+    h.stream.synchronize()
+    for i in range(n_t):
+        assert np.array_equal(to_numpy(h.chain.placeholder(i)), x_np[i]), i
+    table = h.chain.pointer_table().cpu().numpy()
+    assert table.tolist() == [t.data_ptr() for t in x_dev]
+    h.close()
