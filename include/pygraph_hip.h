@@ -184,6 +184,17 @@ pg_status pg_time_loop(pg_chain *chain, int32_t mode, const uint8_t *mode_per_se
                        const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
                        double *us_per_iter_out);
 
+/* GPU execution time of each kernel: launches kernels [k_begin, k_end) eagerly (as pg_eager_range
+ * does), each with a pair of events that take the kernel's own start and end timestamps,
+ * synchronises the stream, and writes k_end - k_begin durations in microseconds to dur_us_out
+ * [host].  For roofline figures: time between launches is not included. */
+pg_status pg_time_kernels(pg_chain *chain, const void *const *ext_dev_ptrs, int32_t k_begin, int32_t k_end,
+                          void *hip_stream, float *dur_us_out);
+
+/* GPU execution time of one copy refresh (the batched copy kernel's launches, summed), measured the
+ * same way; *dur_us_out [host] in microseconds.  Synchronises the stream. */
+pg_status pg_time_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream, float *dur_us_out);
+
 /* Accessors.  Host only. */
 pg_status pg_chain_int_buffer(const pg_chain *chain, int32_t int_index, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_placeholder(const pg_chain *chain, int32_t ext_index, void **dev_ptr_out, size_t *bytes_out);

@@ -71,6 +71,8 @@ def lib():
             getattr(L, name).argtypes = [vp, PP, vp]
         L.pg_eager_range.argtypes = [vp, PP, i32, i32, vp]
         L.pg_select.argtypes = [C.POINTER(C.c_double), i32, C.POINTER(C.c_uint8)]
+        L.pg_time_kernels.argtypes = [vp, PP, i32, i32, vp, C.POINTER(C.c_float)]
+        L.pg_time_refresh_copy.argtypes = [vp, PP, vp, C.POINTER(C.c_float)]
         L.pg_profile.argtypes = [vp, PP, vp, i32, i32, C.POINTER(C.c_double)]
         L.pg_run_selected.argtypes = [vp, C.POINTER(C.c_uint8), PP, vp]
         L.pg_time_loop.argtypes = [vp, i32, C.POINTER(C.c_uint8), PP, i32, i32, vp, C.POINTER(C.c_double)]
@@ -267,6 +269,19 @@ class Chain:
             mp = modes.ctypes.data_as(C.POINTER(C.c_uint8))
         us = C.c_double(0)
         _check(lib().pg_time_loop(self._h, mode, mp, flat, n_sets, iters, self._s(stream), C.byref(us)))
+        return us.value
+
+    def time_kernels(self, ext, stream, k_begin: int = 0, k_end: Optional[int] = None) -> np.ndarray:
+        """GPU execution time (microseconds) of each kernel in [k_begin, k_end), launched eagerly."""
+        k_end = len(self.spec.kernels) if k_end is None else k_end
+        out = np.zeros(max(0, k_end - k_begin), np.float32)
+        _check(lib().pg_time_kernels(self._h, self._ext(ext), k_begin, k_end, self._s(stream),
+                                     out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def time_refresh_copy(self, ext, stream) -> float:
+        us = C.c_float(0)
+        _check(lib().pg_time_refresh_copy(self._h, self._ext(ext), self._s(stream), C.byref(us)))
         return us.value
 
     def set_table_refresh(self, how: int):

@@ -8,6 +8,8 @@
 #include "../../include/pygraph_hip.h"
 #include "kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 #include <chrono>
 #include <cmath>
@@ -698,6 +700,73 @@ pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segmen
     PG_HIP(hipStreamSynchronize(s));
     *us_out = (now_us() - t0) / iters;
     return PG_OK;
+}
+
+// Launch with start/stop events that take the kernel's own dispatch timestamps.
+static pg_status launch_timed(const void* fn, dim3 grid, dim3 block, void* argblock, hipStream_t s,
+                              std::vector<hipEvent_t>& evs) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    PG_HIP(hipEventCreate(&e0));
+    evs.push_back(e0);
+    PG_HIP(hipEventCreate(&e1));
+    evs.push_back(e1);
+    void* args[1] = {argblock};
+    PG_HIP(hipExtLaunchKernel(fn, grid, block, args, 0, s, e0, e1, 0));
+    return PG_OK;
+}
+
+static pg_status collect_timed(std::vector<hipEvent_t>& evs, hipStream_t s, float* dur_us, bool sum_all) {
+    pg_status st = PG_OK;
+    hipError_t e = hipStreamSynchronize(s);
+    if (e != hipSuccess) { g_hip_err = (int)e; st = fail(PG_EHIP, "hipStreamSynchronize failed: %s", hipGetErrorString(e)); }
+    if (sum_all && dur_us) *dur_us = 0.f;
+    for (size_t i = 0; i + 1 < evs.size() && st == PG_OK; i += 2) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, evs[i], evs[i + 1]);
+        if (e != hipSuccess) { g_hip_err = (int)e; st = fail(PG_EHIP, "hipEventElapsedTime failed: %s", hipGetErrorString(e)); break; }
+        if (sum_all) *dur_us += ms * 1000.f; else dur_us[i / 2] = ms * 1000.f;
+    }
+    for (hipEvent_t ev : evs) (void)hipEventDestroy(ev);
+    evs.clear();
+    return st;
+}
+
+pg_status pg_time_kernels(pg_chain* c, const void* const* ext, int32_t k0, int32_t k1, void* hip_stream, float* dur_us_out) {
+    pg_status st = check_call(c, ext, hip_stream, false);
+    if (st) return st;
+    if (k0 < 0 || k1 < k0 || k1 > (int)c->k.size() || !dur_us_out) return fail(PG_EINVAL, "bad kernel range or null output");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<hipEvent_t> evs;
+    evs.reserve(2 * (size_t)(k1 - k0));
+    for (int i = k0; i < k1 && st == PG_OK; i++) {
+        KernelRec& r = c->rec[i];
+        for (int j = 0; j < r.n_in; j++)
+            if (r.ext_of[j] >= 0) r.a_eager.ptr[1 + j] = ext[r.ext_of[j]];
+        st = launch_timed(r.direct.fn, r.direct.grid, r.direct.block, &r.a_eager, s, evs);
+    }
+    pg_status st2 = collect_timed(evs, s, dur_us_out, false);
+    return st ? st : st2;
+}
+
+pg_status pg_time_refresh_copy(pg_chain* c, const void* const* ext, void* hip_stream, float* dur_us_out) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    if (!dur_us_out) return fail(PG_EINVAL, "null output");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    CopyList& L = c->copy_lists[0];
+    std::vector<hipEvent_t> evs;
+    for (const auto& g : L.groups) {
+        if (g.c1 == g.c0 || st != PG_OK) continue;
+        pgk::CopyArgs a;
+        a.chunks = reinterpret_cast<const pgk::CopyChunk*>(c->ws + L.chunks_off) + g.c0;
+        a.tensors = reinterpret_cast<const pgk::CopyTensor*>(c->ws + L.tensors_off);
+        a.src_base = g.t0;
+        a.n_chunks = g.c1 - g.c0;
+        for (int t = g.t0; t < g.t1; t++) a.src[t - g.t0] = ext[L.ext[t]];
+        st = launch_timed(pgk::copy_kernel(), dim3((unsigned)a.n_chunks), dim3(256), &a, s, evs);
+    }
+    pg_status st2 = collect_timed(evs, s, dur_us_out, true);
+    return st ? st : st2;
 }
 
 pg_status pg_chain_int_buffer(const pg_chain* c, int32_t i, void** p, size_t* bytes) {
