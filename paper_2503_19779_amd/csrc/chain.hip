@@ -319,18 +319,12 @@ pg_status make_records(pg_chain* c) {
                 break;
             }
         }
-        dim3 grid, block;
-        switch (d.op) {
-        case PG_ADD: case PG_MUL: case PG_GELU: pgk::shape_elementwise(d.dtype, d.n, &grid, &block); break;
-        case PG_RMSNORM: pgk::shape_rmsnorm((int)d.rows, &grid, &block); break;
-        case PG_GEMV: pgk::shape_gemv((int)d.rows, (int)d.n, &grid, &block); break;
-        default: pgk::shape_sbr(d.dtype, d.n, &grid, &block); break;
-        }
-        r.direct.fn = pgk::kernel_for(d.op, d.dtype, 0);
-        r.indirect.fn = pgk::kernel_for(d.op, d.dtype, r.ind_mask);
-        if (!r.direct.fn || !r.indirect.fn) return fail(PG_EINVAL, "kernel %d: no device kernel for op %d dtype %d", i, d.op, d.dtype);
-        r.direct.grid = r.indirect.grid = grid;
-        r.direct.block = r.indirect.block = block;
+        pgk::Shape sh;
+        sh.n = d.n; sh.m = d.m ? d.m : d.n; sh.rows = d.rows; sh.cols = d.cols; sh.inner = d.inner;
+        if (!pgk::plan(d.op, d.dtype, 0, sh, &r.direct) || !pgk::plan(d.op, d.dtype, r.ind_mask, sh, &r.indirect))
+            return fail(PG_EINVAL, "kernel %d: no device kernel for op %d dtype %d", i, d.op, d.dtype);
+        if (r.direct.grid.x != r.indirect.grid.x || r.direct.block.x != r.indirect.block.x)
+            return fail(PG_EINVAL, "kernel %d: direct and indirect forms disagree on the launch shape", i);
     }
     return PG_OK;
 }

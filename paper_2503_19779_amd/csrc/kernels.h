@@ -76,15 +76,15 @@ struct Launch {
     dim3 block{1, 1, 1};
 };
 
-// Kernel handle for (op, dtype, mask of indirected operands); nullptr if there is none.
-const void* kernel_for(int op, int dtype, int ind_mask);
+struct Shape {
+    long long n = 0, m = 0, rows = 1, cols = 0, inner = 0;
+};
+
+// Kernel instantiation and launch shape for (op, dtype, mask of indirected operands, shape).  The
+// choice depends on the shape alone, never on the mask or on pointer values, so the direct and the
+// indirect form of a kernel run the same schedule.  False if there is no such kernel.
+bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out);
 const void* copy_kernel();
 const void* table_kernel();
-
-// Launch shape; identical for every variant of a kernel so that all modes run the same schedule.
-void shape_elementwise(int dtype, long long n, dim3* grid, dim3* block);
-void shape_rmsnorm(int rows, dim3* grid, dim3* block);
-void shape_gemv(int rows, int n, dim3* grid, dim3* block);
-void shape_sbr(int dtype, long long n, dim3* grid, dim3* block);
 
 }  // namespace pgk

@@ -6,15 +6,23 @@
 // forms (an operand is the address of a pointer-table slot that the kernel dereferences first;
 // paper, Sec. 3 "Parameter Indirection" and Sec. 4 "Kernel generation": the body is unchanged,
 // only a dereference prologue is added).  All forms of a kernel are instantiations of one body
-// with one launch shape, so every replay mode computes bit-identical results.  The translation
-// unit is built with -ffp-contract=off: fused multiply-adds appear only where written.
+// with one launch shape, so every replay mode computes bit-identical results.
+//
+// The chain's kernels are short (a few microseconds), so their cost is latency, not throughput:
+// each shape class gets its own small instantiation (picked on the host from the shape alone, never
+// from a pointer value), all loads are issued before the first use, and work is spread over lanes
+// rather than looped inside one.  A misaligned external tensor changes only how a 16-byte vector is
+// fetched (element loads instead of one vector load), never which lane adds what in which order, so
+// results do not depend on alignment either.
+//
+// The translation unit is built with -ffp-contract=off: fused multiply-adds appear only where
+// written.
 #include "kernels.h"
 
 namespace pgk {
 namespace {
 
 constexpr int kBlock = 256;   // threads per workgroup = 4 waves of 64
-constexpr int kUnroll = 4;    // 16-byte vectors per thread kept in flight
 
 // ---- operand resolution -------------------------------------------------------------------
 template <bool IND>
@@ -26,13 +34,11 @@ __device__ __forceinline__ const void* resolve(const void* p) {
     }
 }
 
-__device__ __forceinline__ bool aligned16(const void* p) {
-    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+__device__ __forceinline__ bool aligned_to(const void* p, unsigned bytes) {
+    return (reinterpret_cast<uintptr_t>(p) & (bytes - 1u)) == 0;
 }
 
 // ---- storage formats ------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_to_f32(unsigned b) { return __uint_as_float(b << 16); }
-
 // round to nearest, ties to even; NaN stays a quiet NaN
 __device__ __forceinline__ unsigned f32_to_bf16(float f) {
     unsigned u = __float_as_uint(f);
@@ -43,37 +49,111 @@ __device__ __forceinline__ unsigned f32_to_bf16(float f) {
 
 typedef unsigned short bf16_t;
 
-template <typename T> struct Fmt;
-template <> struct Fmt<float> {
-    static constexpr int N = 4;   // elements per 16-byte vector
-    static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
-        f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+// A "vector" is VB bytes (16 or 4) = NV elements, carried in NW 32-bit words.
+template <typename T, int VB> struct Vec;
+template <int VB> struct Vec<float, VB> {
+    static constexpr int NV = VB / 4, NW = VB / 4;
+    static __device__ __forceinline__ void unpack(const unsigned* w, float* f) {
+#pragma unroll
+        for (int i = 0; i < NV; i++) f[i] = __uint_as_float(w[i]);
     }
-    static __device__ __forceinline__ uint4 pack(const float* f) {
-        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    static __device__ __forceinline__ void pack(const float* f, unsigned* w) {
+#pragma unroll
+        for (int i = 0; i < NV; i++) w[i] = __float_as_uint(f[i]);
     }
-    static __device__ __forceinline__ float load(const float* p) { return *p; }
-    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
 };
-template <> struct Fmt<bf16_t> {
-    static constexpr int N = 8;
-    static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
-        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
-        f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
-        f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+template <int VB> struct Vec<bf16_t, VB> {
+    static constexpr int NV = VB / 2, NW = VB / 4;
+    static __device__ __forceinline__ void unpack(const unsigned* w, float* f) {
+#pragma unroll
+        for (int i = 0; i < NW; i++) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
     }
-    static __device__ __forceinline__ uint4 pack(const float* f) {
-        return make_uint4(f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16), f32_to_bf16(f[2]) | (f32_to_bf16(f[3]) << 16),
-                          f32_to_bf16(f[4]) | (f32_to_bf16(f[5]) << 16), f32_to_bf16(f[6]) | (f32_to_bf16(f[7]) << 16));
+    static __device__ __forceinline__ void pack(const float* f, unsigned* w) {
+#pragma unroll
+        for (int i = 0; i < NW; i++) w[i] = f32_to_bf16(f[2 * i]) | (f32_to_bf16(f[2 * i + 1]) << 16);
     }
-    static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
-    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
 };
 
-template <typename T> __device__ __forceinline__ uint4 ld16(const T* p) { return *reinterpret_cast<const uint4*>(p); }
-template <typename T> __device__ __forceinline__ void st16(T* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
+__device__ __forceinline__ unsigned load_raw(const float* p) { return *reinterpret_cast<const unsigned*>(p); }
+__device__ __forceinline__ unsigned load_raw(const bf16_t* p) { return *p; }
+template <typename T> __device__ __forceinline__ float from_raw(unsigned r) {
+    return __uint_as_float(sizeof(T) == 4 ? r : r << 16);
+}
+__device__ __forceinline__ float load_elem(const float* p) { return *p; }
+__device__ __forceinline__ float load_elem(const bf16_t* p) { return __uint_as_float((unsigned)*p << 16); }
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// Fetch one vector of VB bytes as words.  AL: the address is VB-aligned; otherwise the same bytes
+// arrive through element-sized loads (a tensor is always element aligned).  Loads only: nothing here
+// consumes the data, so a caller can issue many of these before the first wait.
+template <typename T, int VB, bool AL, bool NT = false>
+__device__ __forceinline__ void load_vec(const T* p, unsigned* w) {
+    constexpr int NW = VB / 4;
+    if constexpr (AL) {
+        if constexpr (VB == 16) {
+            v4u t;
+            if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+            else t = *reinterpret_cast<const v4u*>(p);
+            w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+        } else {
+            w[0] = *reinterpret_cast<const unsigned*>(p);
+        }
+    } else if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < NW; i++) w[i] = reinterpret_cast<const unsigned*>(p)[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < NW; i++)
+            w[i] = (unsigned)reinterpret_cast<const unsigned short*>(p)[2 * i] |
+                   ((unsigned)reinterpret_cast<const unsigned short*>(p)[2 * i + 1] << 16);
+    }
+}
+
+// Rows of `cols` elements in 16-byte vectors: nfull = cols / NV full vectors, then (RAGGED shapes
+// only) one partial vector.  Fetching is split in two so that all loads of a kernel can be in flight
+// together: row_vec_issue loads vector min(v, nfull-1) -- always inside the row, no branch -- and
+// row_vec_finish unpacks it, zeroes it if v lies beyond the full vectors, and reads the partial
+// vector's elements one by one.
+template <typename T, bool AL, bool NT = false>
+__device__ __forceinline__ void row_vec_issue(const T* row, int nfull, int v, unsigned* w) {
+    constexpr int NV = Vec<T, 16>::NV;
+    const int vc = v < nfull ? v : nfull - 1;
+    load_vec<T, 16, AL, NT>(row + (size_t)vc * NV, w);
+}
+template <typename T, bool RAGGED>
+__device__ __forceinline__ void row_vec_finish(const T* row, int cols, int nfull, int v, const unsigned* w, float* f) {
+    constexpr int NV = Vec<T, 16>::NV;
+    Vec<T, 16>::unpack(w, f);
+    if (v >= nfull) {
+#pragma unroll
+        for (int i = 0; i < NV; i++) f[i] = 0.f;
+        if constexpr (RAGGED) {
+            if (v == nfull) {
+                const int left = cols - nfull * NV;
+#pragma unroll
+                for (int i = 0; i < NV; i++)
+                    if (i < left) f[i] = load_elem(row + (size_t)nfull * NV + i);
+            }
+        }
+    }
+}
+
+template <int VB>
+__device__ __forceinline__ void store_vec(void* p, const unsigned* w) {
+    if constexpr (VB == 16) {
+        v4u t;
+        t.x = w[0]; t.y = w[1]; t.z = w[2]; t.w = w[3];
+        *reinterpret_cast<v4u*>(p) = t;
+    } else {
+        *reinterpret_cast<unsigned*>(p) = w[0];
+    }
+}
 
 // ---- wave64 reduction -----------------------------------------------------------------------
 // Butterfly over the 16 lanes of a DPP row, then the four row sums are read out and added in a
@@ -116,66 +196,76 @@ __device__ __forceinline__ float ew_apply(float a, float b) {
     }
 }
 
-template <typename T, int OP, typename IdxT>
-__device__ __forceinline__ void ew_body(const T* a, const T* __restrict__ b, T* o, IdxT n, IdxT m) {   // o may alias a
-    constexpr int N = Fmt<T>::N;
+// Each lane owns U vectors of VB bytes, 256 lanes apart; one block also does the n % NV trailing
+// elements.  `o` may alias `a` (in place): a lane reads what it later overwrites.  AL: a (and b,
+// when it is read by vectors) are VB-aligned.
+template <typename T, int OP, int VB, int U, typename IdxT, bool AL>
+__device__ __forceinline__ void ew_body(const T* a, const T* b, T* o, IdxT n, IdxT m, bool b_vec) {
+    using V = Vec<T, VB>;
+    constexpr int NV = V::NV, NW = V::NW;
     constexpr bool kBinary = (OP != kGelu);
-    const bool vec_ok = aligned16(a) && aligned16(o) && (!kBinary || (aligned16(b) && (m % N) == 0));
-    if (vec_ok) {
-        const IdxT nvec = n / N;
-        const IdxT base = (IdxT)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
-        uint4 ra[kUnroll], rb[kUnroll];
+    constexpr bool kWide = sizeof(T) == 4;
+    const IdxT nvec = n / NV;
+    const IdxT base = (IdxT)blockIdx.x * (kBlock * U) + threadIdx.x;
+    unsigned wa[U][NW], wb[U][NW], rb[U][NV];
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const IdxT v = base + (IdxT)u * kBlock;
-            if (v < nvec) {
-                ra[u] = ld16(a + v * N);
-                if constexpr (kBinary) {
-                    const IdxT bi = (m == n) ? v * N : (v * N) % m;
-                    rb[u] = ld16(b + bi);
+    for (int u = 0; u < U; u++) {
+        const IdxT v = base + (IdxT)u * kBlock;
+        if (v < nvec) {
+            load_vec<T, VB, AL>(a + v * NV, wa[u]);
+            if constexpr (kBinary) {
+                const IdxT i0 = v * NV;
+                if (b_vec) {
+                    load_vec<T, VB, AL>(b + ((m == n) ? i0 : i0 % m), wb[u]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < NV; e++) rb[u][e] = load_raw(b + (i0 + e) % m);
                 }
             }
         }
+    }
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const IdxT v = base + (IdxT)u * kBlock;
-            if (v < nvec) {
-                float fa[N], fb[N], fo[N];
-                Fmt<T>::unpack(ra[u], fa);
-                if constexpr (kBinary) Fmt<T>::unpack(rb[u], fb);
+    for (int u = 0; u < U; u++) {
+        const IdxT v = base + (IdxT)u * kBlock;
+        if (v < nvec) {
+            float fa[NV], fb[NV], fo[NV];
+            unsigned wo[NW];
+            V::unpack(wa[u], fa);
+            if constexpr (kBinary) {
+                if (b_vec) V::unpack(wb[u], fb);
+                else
 #pragma unroll
-                for (int e = 0; e < N; e++) fo[e] = ew_apply<OP, sizeof(T) == 4>(fa[e], kBinary ? fb[e] : 0.f);
-                st16(o + v * N, Fmt<T>::pack(fo));
+                    for (int e = 0; e < NV; e++) fb[e] = from_raw<T>(rb[u][e]);
             }
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = ew_apply<OP, kWide>(fa[e], kBinary ? fb[e] : 0.f);
+            V::pack(fo, wo);
+            store_vec<VB>(o + v * NV, wo);
         }
-        if (blockIdx.x == nvec / (kBlock * kUnroll)) {   // fewer than N trailing elements: the block that owns vector index nvec
-            const IdxT i = nvec * N + threadIdx.x;
-            if (i < n) {
-                const float fb1 = kBinary ? Fmt<T>::load(b + (i % m)) : 0.f;
-                Fmt<T>::store(o + i, ew_apply<OP, sizeof(T) == 4>(Fmt<T>::load(a + i), fb1));
+    }
+    if constexpr (NV > 1) {
+        if (blockIdx.x == nvec / (kBlock * U)) {   // the block that would own vector index nvec
+            const IdxT i = nvec * NV + threadIdx.x;
+            if (threadIdx.x < NV && i < n) {
+                const float fb1 = kBinary ? load_elem(b + (i % m)) : 0.f;
+                store_elem(o + i, ew_apply<OP, kWide>(load_elem(a + i), fb1));
             }
-        }
-    } else {
-        const IdxT tile = (IdxT)kBlock * kUnroll * N;
-        const IdxT start = (IdxT)blockIdx.x * tile;
-        const IdxT end = (n - start < tile) ? n : start + tile;
-        for (IdxT i = start + threadIdx.x; i < end; i += kBlock) {
-            const float fb1 = kBinary ? Fmt<T>::load(b + (i % m)) : 0.f;
-            Fmt<T>::store(o + i, ew_apply<OP, sizeof(T) == 4>(Fmt<T>::load(a + i), fb1));
         }
     }
 }
 
-template <typename T, int OP, int IND>
+template <typename T, int OP, int IND, int VB, int U, typename IdxT>
 __global__ __launch_bounds__(kBlock) void k_elementwise(EwArgs p) {
+    constexpr bool kBinary = (OP != kGelu);
+    constexpr int NV = Vec<T, VB>::NV;
     const T* a = static_cast<const T*>(resolve<(IND & 1) != 0>(p.a));
-    const T* b = (OP != kGelu) ? static_cast<const T*>(resolve<(IND & 2) != 0>(p.b)) : nullptr;
+    const T* b = kBinary ? static_cast<const T*>(resolve<(IND & 2) != 0>(p.b)) : nullptr;
     T* o = static_cast<T*>(p.out);
-    if (p.n < (1ll << 31)) {
-        ew_body<T, OP, unsigned>(a, b, o, (unsigned)p.n, (unsigned)p.m);
-    } else {
-        ew_body<T, OP, unsigned long long>(a, b, o, (unsigned long long)p.n, (unsigned long long)p.m);
-    }
+    const IdxT n = (IdxT)p.n, m = (IdxT)p.m;
+    const bool b_vec = kBinary && (m % NV) == 0;      // then a vector of b never wraps around the period
+    const bool al = aligned_to(a, VB) && (!b_vec || aligned_to(b, VB));
+    if (al) ew_body<T, OP, VB, U, IdxT, true>(a, b, o, n, m, b_vec);
+    else ew_body<T, OP, VB, U, IdxT, false>(a, b, o, n, m, b_vec);
 }
 
 // ---- per-channel scale + bias + ReLU on [N, C, inner] ---------------------------------------
@@ -184,210 +274,278 @@ __device__ __forceinline__ float sbr_apply(float x, float s, float b) {
     return v > 0.f ? v : 0.f;
 }
 
-template <typename T, typename IdxT>
-__device__ __forceinline__ void sbr_body(const T* x /* o may alias x */, const T* __restrict__ s, const T* __restrict__ b, T* o,
-                                         IdxT n, unsigned inner, unsigned channels) {
-    constexpr int N = Fmt<T>::N;
-    const bool vec_ok = aligned16(x) && aligned16(o) && (inner % N) == 0;
-    if (vec_ok) {
-        const IdxT nvec = n / N;   // n is a multiple of inner, hence of N
-        const IdxT base = (IdxT)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
-        uint4 rx[kUnroll];
-        float fs[kUnroll], fbv[kUnroll];
+// VEC: inner is a multiple of the 16-byte vector, so a vector never straddles two channels.
+template <typename T, bool VEC, int U, typename IdxT, bool AL>
+__device__ __forceinline__ void sbr_body(const T* x, const T* s, const T* b, T* o, IdxT n, unsigned inner, unsigned channels) {
+    using V = Vec<T, 16>;
+    constexpr int NV = VEC ? V::NV : 1;
+    const IdxT nvec = n / NV;      // n is a multiple of inner, hence of NV
+    const IdxT base = (IdxT)blockIdx.x * (kBlock * U) + threadIdx.x;
+    unsigned wx[U][4], rs[U], rbv[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const IdxT v = base + (IdxT)u * kBlock;
-            if (v < nvec) {
-                rx[u] = ld16(x + v * N);
-                const unsigned c = (unsigned)(((v * N) / inner) % channels);
-                fs[u] = Fmt<T>::load(s + c);
-                fbv[u] = Fmt<T>::load(b + c);
-            }
+    for (int u = 0; u < U; u++) {
+        const IdxT v = base + (IdxT)u * kBlock;
+        if (v < nvec) {
+            if constexpr (VEC) load_vec<T, 16, AL>(x + v * NV, wx[u]);
+            else wx[u][0] = load_raw(x + v);
+            const unsigned c = (unsigned)(((v * NV) / inner) % channels);
+            rs[u] = load_raw(s + c);
+            rbv[u] = load_raw(b + c);
         }
+    }
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const IdxT v = base + (IdxT)u * kBlock;
-            if (v < nvec) {
-                float fx[N], fo[N];
-                Fmt<T>::unpack(rx[u], fx);
+    for (int u = 0; u < U; u++) {
+        const IdxT v = base + (IdxT)u * kBlock;
+        if (v < nvec) {
+            const float fs = from_raw<T>(rs[u]), fb = from_raw<T>(rbv[u]);
+            if constexpr (VEC) {
+                float fx[V::NV], fo[V::NV];
+                unsigned wo[V::NW];
+                V::unpack(wx[u], fx);
 #pragma unroll
-                for (int e = 0; e < N; e++) fo[e] = sbr_apply(fx[e], fs[u], fbv[u]);
-                st16(o + v * N, Fmt<T>::pack(fo));
+                for (int e = 0; e < V::NV; e++) fo[e] = sbr_apply(fx[e], fs, fb);
+                V::pack(fo, wo);
+                store_vec<16>(o + v * NV, wo);
+            } else {
+                store_elem(o + v, sbr_apply(from_raw<T>(wx[u][0]), fs, fb));
             }
-        }
-    } else {
-        const IdxT tile = (IdxT)kBlock * kUnroll * N;
-        const IdxT start = (IdxT)blockIdx.x * tile;
-        const IdxT end = (n - start < tile) ? n : start + tile;
-        for (IdxT i = start + threadIdx.x; i < end; i += kBlock) {
-            const unsigned c = (unsigned)((i / inner) % channels);
-            Fmt<T>::store(o + i, sbr_apply(Fmt<T>::load(x + i), Fmt<T>::load(s + c), Fmt<T>::load(b + c)));
         }
     }
 }
 
-template <typename T, int IND>
+template <typename T, int IND, bool VEC, int U, typename IdxT>
 __global__ __launch_bounds__(kBlock) void k_scale_bias_relu(SbrArgs p) {
     const T* x = static_cast<const T*>(resolve<(IND & 1) != 0>(p.x));
     const T* s = static_cast<const T*>(resolve<(IND & 2) != 0>(p.s));
     const T* b = static_cast<const T*>(resolve<(IND & 4) != 0>(p.b));
     T* o = static_cast<T*>(p.out);
-    if (p.n < (1ll << 31)) {
-        sbr_body<T, unsigned>(x, s, b, o, (unsigned)p.n, p.inner, p.channels);
-    } else {
-        sbr_body<T, unsigned long long>(x, s, b, o, (unsigned long long)p.n, p.inner, p.channels);
-    }
+    if (!VEC || aligned_to(x, 16)) sbr_body<T, VEC, U, IdxT, true>(x, s, b, o, (IdxT)p.n, p.inner, p.channels);
+    else sbr_body<T, VEC, U, IdxT, false>(x, s, b, o, (IdxT)p.n, p.inner, p.channels);
 }
 
 // ---- RMSNorm: one workgroup per row ------------------------------------------------------------
-// Sum of squares: each thread accumulates its elements with fused multiply-adds, a wave64
-// shuffle reduction follows, the four wave sums are staged through LDS and added in a fixed
-// order by every thread.  Up to kKeep vectors per thread stay in registers between the two
-// passes (hidden <= 8192 for bf16), longer rows are read again.
-template <typename T, int IND>
-__global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
-    constexpr int N = Fmt<T>::N;
-    constexpr int kKeep = 4;
-    const int cols = p.cols;
-    const size_t row = blockIdx.x;
-    const T* __restrict__ x = static_cast<const T*>(resolve<(IND & 1) != 0>(p.x)) + row * cols;
-    const T* __restrict__ g = static_cast<const T*>(resolve<(IND & 2) != 0>(p.g));
-    T* o = static_cast<T*>(p.out) + row * cols;
-    const int tid = threadIdx.x;
-    const bool vec_ok = aligned16(x) && aligned16(g) && aligned16(o) && (cols % N) == 0;
-    const int nvec = cols / N;
-    uint4 keep[kKeep];
-    float acc = 0.f;
-    if (vec_ok) {
+// Each thread keeps its VPT vectors of x and of the gain in registers (all fetched up front), sums
+// squares with fused multiply-adds, a wave64 shuffle reduction follows, the four wave sums are
+// staged through LDS and added in a fixed order by every thread.  VPT = 0 is the long-row form: it
+// loops and reads x a second time.
+template <typename T, bool RAGGED>
+__device__ __forceinline__ void rms_store(T* o, int cols, int nfull, int v, bool al_o, const float* fo) {
+    constexpr int NV = Vec<T, 16>::NV;
+    if (v < nfull && (al_o || !RAGGED)) {
+        unsigned w[4];
+        Vec<T, 16>::pack(fo, w);
+        store_vec<16>(o + (size_t)v * NV, w);
+    } else if constexpr (RAGGED) {
+        const int left = cols - v * NV;
 #pragma unroll
-        for (int u = 0; u < kKeep; u++) {
-            const int v = tid + u * kBlock;
-            if (v < nvec) keep[u] = ld16(x + (size_t)v * N);
-        }
-#pragma unroll
-        for (int u = 0; u < kKeep; u++) {
-            const int v = tid + u * kBlock;
-            if (v < nvec) {
-                float f[N];
-                Fmt<T>::unpack(keep[u], f);
-#pragma unroll
-                for (int e = 0; e < N; e++) acc = __builtin_fmaf(f[e], f[e], acc);
-            }
-        }
-        for (int v = tid + kKeep * kBlock; v < nvec; v += kBlock) {
-            float f[N];
-            Fmt<T>::unpack(ld16(x + (size_t)v * N), f);
-#pragma unroll
-            for (int e = 0; e < N; e++) acc = __builtin_fmaf(f[e], f[e], acc);
-        }
-    } else {
-        for (int i = tid; i < cols; i += kBlock) {
-            const float f = Fmt<T>::load(x + i);
-            acc = __builtin_fmaf(f, f, acc);
-        }
-    }
-    acc = wave_sum(acc);
-    __shared__ float part[kBlock / 64];
-    if ((tid & 63) == 0) part[tid >> 6] = acc;
-    __syncthreads();
-    const float total = ((part[0] + part[1]) + part[2]) + part[3];
-    const float scale = 1.0f / sqrtf(total / (float)cols + p.eps);
-    if (vec_ok) {
-#pragma unroll
-        for (int u = 0; u < kKeep; u++) {
-            const int v = tid + u * kBlock;
-            if (v < nvec) {
-                float f[N], fg[N], fo[N];
-                Fmt<T>::unpack(keep[u], f);
-                Fmt<T>::unpack(ld16(g + (size_t)v * N), fg);
-#pragma unroll
-                for (int e = 0; e < N; e++) fo[e] = (f[e] * scale) * fg[e];
-                st16(o + (size_t)v * N, Fmt<T>::pack(fo));
-            }
-        }
-        for (int v = tid + kKeep * kBlock; v < nvec; v += kBlock) {
-            float f[N], fg[N], fo[N];
-            Fmt<T>::unpack(ld16(x + (size_t)v * N), f);
-            Fmt<T>::unpack(ld16(g + (size_t)v * N), fg);
-#pragma unroll
-            for (int e = 0; e < N; e++) fo[e] = (f[e] * scale) * fg[e];
-            st16(o + (size_t)v * N, Fmt<T>::pack(fo));
-        }
-    } else {
-        for (int i = tid; i < cols; i += kBlock)
-            Fmt<T>::store(o + i, (Fmt<T>::load(x + i) * scale) * Fmt<T>::load(g + i));
+        for (int e = 0; e < NV; e++)
+            if (e < left) store_elem(o + (size_t)v * NV + e, fo[e]);
     }
 }
 
-// ---- GEMV: one wave per output column, rows of h in blocks of kRowBlock ------------------------
-// Memory-bound: the weight row is streamed once with 16-byte loads (four per lane in flight for
-// 2048 columns), multiplied into fp32 accumulators, and reduced across the wave.  No MFMA: at
-// batch 1 there is no reuse to feed a matrix core.
-constexpr int kRowBlock = 4;
+template <typename T, int VPT, bool RAGGED, bool AL>
+__device__ __forceinline__ void rms_body(const T* x, const T* g, T* o, int cols, float eps, bool al_o, float* part) {
+    constexpr int NV = Vec<T, 16>::NV;
+    const int tid = threadIdx.x;
+    const int nfull = cols / NV;
+    float acc = 0.f;
+    if constexpr (VPT > 0) {
+        unsigned wx[VPT][4], wg[VPT][4];
+        float fx[VPT][NV], fg[VPT][NV];
+        if (!RAGGED || nfull > 0) {
+#pragma unroll
+            for (int u = 0; u < VPT; u++) {
+                row_vec_issue<T, AL>(x, nfull, tid + u * kBlock, wx[u]);
+                row_vec_issue<T, AL>(g, nfull, tid + u * kBlock, wg[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < VPT; u++) {
+            row_vec_finish<T, RAGGED>(x, cols, nfull, tid + u * kBlock, wx[u], fx[u]);
+#pragma unroll
+            for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fx[u][e], fx[u][e], acc);
+        }
+        acc = wave_sum(acc);
+        if ((tid & 63) == 0) part[tid >> 6] = acc;
+        __syncthreads();
+        const float total = ((part[0] + part[1]) + part[2]) + part[3];
+        const float scale = 1.0f / sqrtf(total / (float)cols + eps);
+#pragma unroll
+        for (int u = 0; u < VPT; u++) {
+            float fo[NV];
+            row_vec_finish<T, RAGGED>(g, cols, nfull, tid + u * kBlock, wg[u], fg[u]);
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = (fx[u][e] * scale) * fg[u][e];
+            rms_store<T, RAGGED>(o, cols, nfull, tid + u * kBlock, al_o, fo);
+        }
+    } else {
+        const int nvec = (cols + NV - 1) / NV;
+        for (int v = tid; v < nvec; v += kBlock) {
+            unsigned w[4];
+            float f[NV];
+            if (!RAGGED || nfull > 0) row_vec_issue<T, AL>(x, nfull, v, w);
+            row_vec_finish<T, RAGGED>(x, cols, nfull, v, w, f);
+#pragma unroll
+            for (int e = 0; e < NV; e++) acc = __builtin_fmaf(f[e], f[e], acc);
+        }
+        acc = wave_sum(acc);
+        if ((tid & 63) == 0) part[tid >> 6] = acc;
+        __syncthreads();
+        const float total = ((part[0] + part[1]) + part[2]) + part[3];
+        const float scale = 1.0f / sqrtf(total / (float)cols + eps);
+        for (int v = tid; v < nvec; v += kBlock) {
+            unsigned w[4], w2[4];
+            float f[NV], fgv[NV], fo[NV];
+            if (!RAGGED || nfull > 0) {
+                row_vec_issue<T, AL>(x, nfull, v, w);
+                row_vec_issue<T, AL>(g, nfull, v, w2);
+            }
+            row_vec_finish<T, RAGGED>(x, cols, nfull, v, w, f);
+            row_vec_finish<T, RAGGED>(g, cols, nfull, v, w2, fgv);
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = (f[e] * scale) * fgv[e];
+            rms_store<T, RAGGED>(o, cols, nfull, v, al_o, fo);
+        }
+    }
+}
 
-template <typename T, int IND>
+template <typename T, int IND, int VPT, bool RAGGED>
+__global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
+    const int cols = p.cols;
+    const size_t row = blockIdx.x;
+    const T* x = static_cast<const T*>(resolve<(IND & 1) != 0>(p.x)) + row * cols;
+    const T* g = static_cast<const T*>(resolve<(IND & 2) != 0>(p.g));
+    T* o = static_cast<T*>(p.out) + row * cols;
+    __shared__ float part[kBlock / 64];
+    // rows of an aligned buffer stay aligned when cols is a multiple of the vector; else check this row
+    const bool al = aligned_to(x, 16) && aligned_to(g, 16);
+    const bool al_o = aligned_to(o, 16);
+    if (al) rms_body<T, VPT, RAGGED, true>(x, g, o, cols, p.eps, al_o, part);
+    else rms_body<T, VPT, RAGGED, false>(x, g, o, cols, p.eps, al_o, part);
+}
+
+// ---- GEMV ------------------------------------------------------------------------------------------
+// Memory-bound: every weight is read exactly once.  One wave computes R output columns (R weight
+// rows): per chunk of 4 * 64 vectors of the row it issues all R * 4 weight loads (non-temporal:
+// streamed, no reuse) and the 4 loads of its slice of h before the first multiply, accumulates in
+// fp32 with fused multiply-adds in a fixed order, and reduces across the wave.  No MFMA: at batch 1
+// there is no reuse to feed a matrix core.
+constexpr int kGemvChunk = 4;   // vectors per lane per chunk
+
+template <typename T, int R, bool RAGGED, bool AL>
+__device__ __forceinline__ void gemv_body(const T* W, const T* h, T* y, int n, int cols, int j0, int lane) {
+    constexpr int NV = Vec<T, 16>::NV;
+    const int nfull = cols / NV;
+    const int nvec = (cols + NV - 1) / NV;
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) acc[r] = 0.f;
+    for (int v0 = 0; v0 < nvec; v0 += 64 * kGemvChunk) {
+        unsigned ww[R][kGemvChunk][4], wh[kGemvChunk][4];
+        const T* wrow[R];
+#pragma unroll
+        for (int r = 0; r < R; r++) wrow[r] = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * cols;   // a ragged last group re-reads the last row
+        if (!RAGGED || nfull > 0) {
+#pragma unroll
+            for (int r = 0; r < R; r++)
+#pragma unroll
+                for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL, true>(wrow[r], nfull, v0 + u * 64 + lane, ww[r][u]);
+#pragma unroll
+            for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(h, nfull, v0 + u * 64 + lane, wh[u]);
+        }
+        float fh[kGemvChunk][NV];
+#pragma unroll
+        for (int u = 0; u < kGemvChunk; u++) row_vec_finish<T, RAGGED>(h, cols, nfull, v0 + u * 64 + lane, wh[u], fh[u]);
+#pragma unroll
+        for (int r = 0; r < R; r++)
+#pragma unroll
+            for (int u = 0; u < kGemvChunk; u++) {
+                float fw[NV];
+                row_vec_finish<T, RAGGED>(wrow[r], cols, nfull, v0 + u * 64 + lane, ww[r][u], fw);
+#pragma unroll
+                for (int e = 0; e < NV; e++) acc[r] = __builtin_fmaf(fw[e], fh[u][e], acc[r]);
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        const float s = wave_sum(acc[r]);
+        if (lane == 0 && j0 + r < n) store_elem(y + j0 + r, s);
+    }
+}
+
+template <typename T, int IND, int R, bool RAGGED>
 __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
-    constexpr int N = Fmt<T>::N;
-    const T* __restrict__ W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
-    const T* __restrict__ h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
+    const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
+    const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
     T* y = static_cast<T*>(p.out);
     const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (j >= p.n) return;   // whole wave leaves together
-    const int cols = p.cols, rows = p.rows;
+    const int j0 = (blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * R;
+    if (j0 >= p.n) return;   // whole wave leaves together
+    // row starts of W stay aligned only if cols is a multiple of the vector
+    const bool al = !RAGGED && aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemv_body<T, R, RAGGED, true>(W, h, y, p.n, p.cols, j0, lane);
+    else gemv_body<T, R, RAGGED, false>(W, h, y, p.n, p.cols, j0, lane);
+}
+
+// Batched (rows > 1): one wave per output column; the weight chunk stays in registers while the
+// rows of h stream past it, kRowBlock rows at a time.
+constexpr int kRowBlock = 4;
+
+template <typename T, bool RAGGED, bool AL>
+__device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int rows, int n, int cols, int j, int lane) {
+    constexpr int NV = Vec<T, 16>::NV;
+    const int nfull = cols / NV;
+    const int nvec = (cols + NV - 1) / NV;
     const T* wrow = W + (size_t)j * cols;
-    const bool vec_ok = aligned16(W) && aligned16(h) && (cols % N) == 0;
-    const int nvec = cols / N;
     for (int r0 = 0; r0 < rows; r0 += kRowBlock) {
         float acc[kRowBlock];
 #pragma unroll
         for (int rr = 0; rr < kRowBlock; rr++) acc[rr] = 0.f;
-        if (vec_ok) {
-            for (int v0 = 0; v0 < nvec; v0 += 64 * kUnroll) {
-                uint4 rw[kUnroll];
+        for (int v0 = 0; v0 < nvec; v0 += 64 * kGemvChunk) {
+            unsigned ww[kGemvChunk][4], wh[kRowBlock][kGemvChunk][4];
+            const T* hrow[kRowBlock];
 #pragma unroll
-                for (int u = 0; u < kUnroll; u++) {
-                    const int v = v0 + u * 64 + lane;
-                    if (v < nvec) rw[u] = ld16(wrow + (size_t)v * N);
-                }
+            for (int rr = 0; rr < kRowBlock; rr++) hrow[rr] = h + (size_t)((r0 + rr < rows) ? r0 + rr : rows - 1) * cols;
+            if (!RAGGED || nfull > 0) {
 #pragma unroll
-                for (int rr = 0; rr < kRowBlock; rr++) {
-                    if (r0 + rr < rows) {
-                        const T* hrow = h + (size_t)(r0 + rr) * cols;
-                        uint4 rh[kUnroll];
-#pragma unroll
-                        for (int u = 0; u < kUnroll; u++) {
-                            const int v = v0 + u * 64 + lane;
-                            if (v < nvec) rh[u] = ld16(hrow + (size_t)v * N);
-                        }
-#pragma unroll
-                        for (int u = 0; u < kUnroll; u++) {
-                            const int v = v0 + u * 64 + lane;
-                            if (v < nvec) {
-                                float fw[N], fh[N];
-                                Fmt<T>::unpack(rw[u], fw);
-                                Fmt<T>::unpack(rh[u], fh);
-#pragma unroll
-                                for (int e = 0; e < N; e++) acc[rr] = __builtin_fmaf(fw[e], fh[e], acc[rr]);
-                            }
-                        }
-                    }
-                }
-            }
-        } else {
-            for (int i = lane; i < cols; i += 64) {
-                const float fw = Fmt<T>::load(wrow + i);
+                for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(wrow, nfull, v0 + u * 64 + lane, ww[u]);
 #pragma unroll
                 for (int rr = 0; rr < kRowBlock; rr++)
-                    if (r0 + rr < rows) acc[rr] = __builtin_fmaf(fw, Fmt<T>::load(h + (size_t)(r0 + rr) * cols + i), acc[rr]);
+#pragma unroll
+                    for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(hrow[rr], nfull, v0 + u * 64 + lane, wh[rr][u]);
             }
+            float fw[kGemvChunk][NV];
+#pragma unroll
+            for (int u = 0; u < kGemvChunk; u++) row_vec_finish<T, RAGGED>(wrow, cols, nfull, v0 + u * 64 + lane, ww[u], fw[u]);
+#pragma unroll
+            for (int rr = 0; rr < kRowBlock; rr++)
+#pragma unroll
+                for (int u = 0; u < kGemvChunk; u++) {
+                    float fh[NV];
+                    row_vec_finish<T, RAGGED>(hrow[rr], cols, nfull, v0 + u * 64 + lane, wh[rr][u], fh);
+#pragma unroll
+                    for (int e = 0; e < NV; e++) acc[rr] = __builtin_fmaf(fw[u][e], fh[e], acc[rr]);
+                }
         }
 #pragma unroll
         for (int rr = 0; rr < kRowBlock; rr++) {
             const float s = wave_sum(acc[rr]);
-            if (lane == 0 && r0 + rr < rows) Fmt<T>::store(y + (size_t)(r0 + rr) * p.n + j, s);
+            if (lane == 0 && r0 + rr < rows) store_elem(y + (size_t)(r0 + rr) * n + j, s);
         }
     }
+}
+
+template <typename T, int IND, bool RAGGED>
+__global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
+    const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
+    const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
+    T* y = static_cast<T*>(p.out);
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (j >= p.n) return;
+    const bool al = !RAGGED && aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemvb_body<T, RAGGED, true>(W, h, y, p.rows, p.n, p.cols, j, lane);
+    else gemvb_body<T, RAGGED, false>(W, h, y, p.rows, p.n, p.cols, j, lane);
 }
 
 // ---- batched multi-tensor copy -----------------------------------------------------------------
@@ -396,7 +554,6 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
 // the source alignment varies: 16-byte aligned sources take 128-bit loads and stores with eight
 // vectors per lane in flight; others fall back to 4-byte or 2-byte moves.
 constexpr int kCopyUnroll = 8;
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(kBlock) void k_copy(CopyArgs p) {
     const CopyChunk c = p.chunks[blockIdx.x];
@@ -446,91 +603,177 @@ __global__ __launch_bounds__(64) void k_table_write(TableArgs p) {
     for (int i = threadIdx.x; i < p.n; i += 64) p.table[p.base + i] = p.ptr[i];
 }
 
+// ---- host side: pick the instantiation and the launch shape from the kernel's shape alone ----------
+#define PG_FN(...) reinterpret_cast<const void*>(&__VA_ARGS__)
+
+unsigned blocks_for(long long n, long long per_block) {
+    const long long g = (n + per_block - 1) / per_block;
+    return (unsigned)(g < 1 ? 1 : g);
+}
+
+template <typename T, int OP, int VB, int U, typename IdxT>
+const void* ew_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_elementwise<T, OP, 0, VB, U, IdxT>);
+    case 1: return PG_FN(k_elementwise<T, OP, 1, VB, U, IdxT>);
+    case 2: if constexpr (OP != kGelu) return PG_FN(k_elementwise<T, OP, 2, VB, U, IdxT>); else return nullptr;
+    case 3: if constexpr (OP != kGelu) return PG_FN(k_elementwise<T, OP, 3, VB, U, IdxT>); else return nullptr;
+    default: return nullptr;
+    }
+}
+
+// Shape classes: (4-byte vectors, 1 per lane) for small GELUs, whose cost is the arithmetic a lane
+// does in sequence; (16-byte, 1 per lane) for short tensors; (16-byte, 4 per lane) for long ones,
+// with 64-bit indices beyond 2^31 elements.
 template <typename T, int OP>
-const void* ew_variant(int ind) {
-    switch (ind) {
-    case 0: return reinterpret_cast<const void*>(&k_elementwise<T, OP, 0>);
-    case 1: return reinterpret_cast<const void*>(&k_elementwise<T, OP, 1>);
-    case 2: return OP == kGelu ? nullptr : reinterpret_cast<const void*>(&k_elementwise<T, OP, 2>);
-    case 3: return OP == kGelu ? nullptr : reinterpret_cast<const void*>(&k_elementwise<T, OP, 3>);
-    default: return nullptr;
+bool plan_ew_t(int ind, long long n, Launch* out) {
+    constexpr int NV16 = 16 / (int)sizeof(T), NV4 = 4 / (int)sizeof(T);
+    const long long bytes = n * (long long)sizeof(T);
+    const bool narrow = OP == kGelu && n <= (sizeof(T) == 4 ? (1ll << 20) : (1ll << 15));
+    out->block = dim3(kBlock);
+    if (narrow) {
+        out->fn = ew_by_ind<T, OP, 4, 1, unsigned>(ind);
+        out->grid = dim3(blocks_for(n, (long long)kBlock * NV4));
+    } else if (bytes <= (256ll << 10)) {
+        out->fn = ew_by_ind<T, OP, 16, 1, unsigned>(ind);
+        out->grid = dim3(blocks_for(n, (long long)kBlock * NV16));
+    } else if (n < (1ll << 31)) {
+        out->fn = ew_by_ind<T, OP, 16, 4, unsigned>(ind);
+        out->grid = dim3(blocks_for(n, (long long)kBlock * 4 * NV16));
+    } else {
+        out->fn = ew_by_ind<T, OP, 16, 4, unsigned long long>(ind);
+        out->grid = dim3(blocks_for(n, (long long)kBlock * 4 * NV16));
+    }
+    return out->fn != nullptr;
+}
+
+template <typename T>
+bool plan_ew(int op, int ind, long long n, Launch* out) {
+    switch (op) {
+    case kAdd: return plan_ew_t<T, kAdd>(ind, n, out);
+    case kMul: return plan_ew_t<T, kMul>(ind, n, out);
+    case kGelu: return plan_ew_t<T, kGelu>(ind, n, out);
+    default: return false;
     }
 }
-template <typename T>
-const void* rms_variant(int ind) {
+
+template <typename T, int VPT, bool RAGGED>
+const void* rms_by_ind(int ind) {
     switch (ind) {
-    case 0: return reinterpret_cast<const void*>(&k_rmsnorm<T, 0>);
-    case 1: return reinterpret_cast<const void*>(&k_rmsnorm<T, 1>);
-    case 2: return reinterpret_cast<const void*>(&k_rmsnorm<T, 2>);
-    case 3: return reinterpret_cast<const void*>(&k_rmsnorm<T, 3>);
-    default: return nullptr;
-    }
-}
-template <typename T>
-const void* gemv_variant(int ind) {
-    switch (ind) {
-    case 0: return reinterpret_cast<const void*>(&k_gemv<T, 0>);
-    case 1: return reinterpret_cast<const void*>(&k_gemv<T, 1>);
-    case 2: return reinterpret_cast<const void*>(&k_gemv<T, 2>);
-    case 3: return reinterpret_cast<const void*>(&k_gemv<T, 3>);
-    default: return nullptr;
-    }
-}
-template <typename T>
-const void* sbr_variant(int ind) {
-    switch (ind) {
-    case 0: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 0>);
-    case 1: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 1>);
-    case 2: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 2>);
-    case 3: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 3>);
-    case 4: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 4>);
-    case 5: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 5>);
-    case 6: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 6>);
-    case 7: return reinterpret_cast<const void*>(&k_scale_bias_relu<T, 7>);
+    case 0: return PG_FN(k_rmsnorm<T, 0, VPT, RAGGED>);
+    case 1: return PG_FN(k_rmsnorm<T, 1, VPT, RAGGED>);
+    case 2: return PG_FN(k_rmsnorm<T, 2, VPT, RAGGED>);
+    case 3: return PG_FN(k_rmsnorm<T, 3, VPT, RAGGED>);
     default: return nullptr;
     }
 }
 
 template <typename T>
-const void* kernel_for_t(int op, int ind) {
-    switch (op) {
-    case kAdd: return ew_variant<T, kAdd>(ind);
-    case kMul: return ew_variant<T, kMul>(ind);
-    case kGelu: return ew_variant<T, kGelu>(ind);
-    case kRmsNorm: return rms_variant<T>(ind);
-    case kGemv: return gemv_variant<T>(ind);
-    case kScaleBiasRelu: return sbr_variant<T>(ind);
+bool plan_rms(int ind, int rows, int cols, Launch* out) {
+    constexpr int NV = 16 / (int)sizeof(T);
+    const int nvec = (cols + NV - 1) / NV;
+    const bool ragged = (cols % NV) != 0;
+    if (nvec <= kBlock) out->fn = ragged ? rms_by_ind<T, 1, true>(ind) : rms_by_ind<T, 1, false>(ind);
+    else if (nvec <= 4 * kBlock) out->fn = ragged ? rms_by_ind<T, 4, true>(ind) : rms_by_ind<T, 4, false>(ind);
+    else out->fn = ragged ? rms_by_ind<T, 0, true>(ind) : rms_by_ind<T, 0, false>(ind);
+    out->grid = dim3((unsigned)rows);
+    out->block = dim3(kBlock);
+    return out->fn != nullptr;
+}
+
+template <typename T, int R, bool RAGGED>
+const void* gemv_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_gemv<T, 0, R, RAGGED>);
+    case 1: return PG_FN(k_gemv<T, 1, R, RAGGED>);
+    case 2: return PG_FN(k_gemv<T, 2, R, RAGGED>);
+    case 3: return PG_FN(k_gemv<T, 3, R, RAGGED>);
     default: return nullptr;
+    }
+}
+template <typename T, bool RAGGED>
+const void* gemvb_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_gemv_batched<T, 0, RAGGED>);
+    case 1: return PG_FN(k_gemv_batched<T, 1, RAGGED>);
+    case 2: return PG_FN(k_gemv_batched<T, 2, RAGGED>);
+    case 3: return PG_FN(k_gemv_batched<T, 3, RAGGED>);
+    default: return nullptr;
+    }
+}
+
+template <typename T>
+bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
+    constexpr int NV = 16 / (int)sizeof(T);
+    const bool ragged = (cols % NV) != 0;
+    out->block = dim3(kBlock);
+    if (rows == 1 && n >= 1024) {
+        // two weight rows per wave once there are enough rows to fill the chip with half the waves
+        out->fn = ragged ? gemv_by_ind<T, 2, true>(ind) : gemv_by_ind<T, 2, false>(ind);
+        out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
+    } else if (rows == 1) {
+        out->fn = ragged ? gemv_by_ind<T, 1, true>(ind) : gemv_by_ind<T, 1, false>(ind);
+        out->grid = dim3(blocks_for(n, kBlock / 64));
+    } else {
+        out->fn = ragged ? gemvb_by_ind<T, true>(ind) : gemvb_by_ind<T, false>(ind);
+        out->grid = dim3(blocks_for(n, kBlock / 64));
+    }
+    return out->fn != nullptr;
+}
+
+template <typename T, bool VEC, int U, typename IdxT>
+const void* sbr_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_scale_bias_relu<T, 0, VEC, U, IdxT>);
+    case 1: return PG_FN(k_scale_bias_relu<T, 1, VEC, U, IdxT>);
+    case 2: return PG_FN(k_scale_bias_relu<T, 2, VEC, U, IdxT>);
+    case 3: return PG_FN(k_scale_bias_relu<T, 3, VEC, U, IdxT>);
+    case 4: return PG_FN(k_scale_bias_relu<T, 4, VEC, U, IdxT>);
+    case 5: return PG_FN(k_scale_bias_relu<T, 5, VEC, U, IdxT>);
+    case 6: return PG_FN(k_scale_bias_relu<T, 6, VEC, U, IdxT>);
+    case 7: return PG_FN(k_scale_bias_relu<T, 7, VEC, U, IdxT>);
+    default: return nullptr;
+    }
+}
+
+template <typename T>
+bool plan_sbr(int ind, long long n, long long inner, Launch* out) {
+    constexpr int NV = 16 / (int)sizeof(T);
+    const bool vec = (inner % NV) == 0;
+    const long long units = vec ? n / NV : n;
+    out->block = dim3(kBlock);
+    if (n >= (1ll << 31)) {
+        out->fn = vec ? sbr_by_ind<T, true, 4, unsigned long long>(ind) : sbr_by_ind<T, false, 4, unsigned long long>(ind);
+        out->grid = dim3(blocks_for(units, kBlock * 4));
+    } else if (units <= 16384) {
+        out->fn = vec ? sbr_by_ind<T, true, 1, unsigned>(ind) : sbr_by_ind<T, false, 1, unsigned>(ind);
+        out->grid = dim3(blocks_for(units, kBlock));
+    } else {
+        out->fn = vec ? sbr_by_ind<T, true, 4, unsigned>(ind) : sbr_by_ind<T, false, 4, unsigned>(ind);
+        out->grid = dim3(blocks_for(units, kBlock * 4));
+    }
+    return out->fn != nullptr;
+}
+
+template <typename T>
+bool plan_t(int op, int ind, const Shape& s, Launch* out) {
+    switch (op) {
+    case kAdd: case kMul: case kGelu: return plan_ew<T>(op, ind, s.n, out);
+    case kRmsNorm: return plan_rms<T>(ind, (int)s.rows, (int)s.cols, out);
+    case kGemv: return plan_gemv<T>(ind, (int)s.rows, (int)s.n, (int)s.cols, out);
+    case kScaleBiasRelu: return plan_sbr<T>(ind, s.n, s.inner, out);
+    default: return false;
     }
 }
 
 }  // namespace
 
-const void* kernel_for(int op, int dtype, int ind_mask) {
-    if (dtype == kF32) return kernel_for_t<float>(op, ind_mask);
-    if (dtype == kBF16) return kernel_for_t<bf16_t>(op, ind_mask);
-    return nullptr;
+bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out) {
+    if (dtype == kF32) return plan_t<float>(op, ind_mask, shape, out);
+    if (dtype == kBF16) return plan_t<bf16_t>(op, ind_mask, shape, out);
+    return false;
 }
 const void* copy_kernel() { return reinterpret_cast<const void*>(&k_copy); }
 const void* table_kernel() { return reinterpret_cast<const void*>(&k_table_write); }
-
-static unsigned blocks_for(long long n, long long per_block) {
-    long long g = (n + per_block - 1) / per_block;
-    return (unsigned)(g < 1 ? 1 : g);
-}
-void shape_elementwise(int dtype, long long n, dim3* grid, dim3* block) {
-    const int N = dtype == kF32 ? 4 : 8;
-    *grid = dim3(blocks_for(n, (long long)kBlock * kUnroll * N));
-    *block = dim3(kBlock);
-}
-void shape_sbr(int dtype, long long n, dim3* grid, dim3* block) { shape_elementwise(dtype, n, grid, block); }
-void shape_rmsnorm(int rows, dim3* grid, dim3* block) {
-    *grid = dim3((unsigned)rows);
-    *block = dim3(kBlock);
-}
-void shape_gemv(int /*rows*/, int n, dim3* grid, dim3* block) {
-    *grid = dim3(blocks_for(n, kBlock / 64));
-    *block = dim3(kBlock);
-}
 
 }  // namespace pgk
