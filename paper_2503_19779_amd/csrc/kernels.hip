@@ -39,13 +39,18 @@ __device__ __forceinline__ bool aligned_to(const void* p, unsigned bytes) {
 }
 
 // ---- storage formats ------------------------------------------------------------------------
-// round to nearest, ties to even; NaN stays a quiet NaN
-__device__ __forceinline__ unsigned f32_to_bf16(float f) {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+// Two fp32 values to a packed pair of bf16: round to nearest, ties to even, NaN stays a quiet NaN.
+// One gfx950 conversion instruction instead of a dozen integer ones: these kernels are latency
+// bound, every instruction on the path from the last load to the store counts.
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
+    v2f x;
+    x.x = lo;
+    x.y = hi;
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(x, v2bf));
 }
+__device__ __forceinline__ unsigned f32_to_bf16(float f) { return pack2_bf16(f, 0.f) & 0xffffu; }
 
 typedef unsigned short bf16_t;
 
@@ -73,7 +78,7 @@ template <int VB> struct Vec<bf16_t, VB> {
     }
     static __device__ __forceinline__ void pack(const float* f, unsigned* w) {
 #pragma unroll
-        for (int i = 0; i < NW; i++) w[i] = f32_to_bf16(f[2 * i]) | (f32_to_bf16(f[2 * i + 1]) << 16);
+        for (int i = 0; i < NW; i++) w[i] = pack2_bf16(f[2 * i], f[2 * i + 1]);
     }
 };
 
@@ -126,22 +131,48 @@ __device__ __forceinline__ void row_vec_issue(const T* row, int nfull, int v, un
     const int vc = v < nfull ? v : nfull - 1;
     load_vec<T, 16, AL, NT>(row + (size_t)vc * NV, w);
 }
+// Words of vector v after the fact: zero beyond the full vectors, and (RAGGED) the partial vector
+// read element by element.
 template <typename T, bool RAGGED>
-__device__ __forceinline__ void row_vec_finish(const T* row, int cols, int nfull, int v, const unsigned* w, float* f) {
+__device__ __forceinline__ void row_vec_fix(const T* row, int cols, int nfull, int v, unsigned* w) {
     constexpr int NV = Vec<T, 16>::NV;
-    Vec<T, 16>::unpack(w, f);
     if (v >= nfull) {
 #pragma unroll
-        for (int i = 0; i < NV; i++) f[i] = 0.f;
+        for (int i = 0; i < 4; i++) w[i] = 0u;
         if constexpr (RAGGED) {
             if (v == nfull) {
                 const int left = cols - nfull * NV;
 #pragma unroll
-                for (int i = 0; i < NV; i++)
-                    if (i < left) f[i] = load_elem(row + (size_t)nfull * NV + i);
+                for (int i = 0; i < NV; i++) {
+                    if (i < left) {
+                        const unsigned r = load_raw(row + (size_t)nfull * NV + i);
+                        if constexpr (sizeof(T) == 4) w[i] = r;
+                        else w[i / 2] |= r << (16 * (i & 1));
+                    }
+                }
             }
         }
     }
+}
+template <typename T, bool RAGGED>
+__device__ __forceinline__ void row_vec_finish(const T* row, int cols, int nfull, int v, unsigned* w, float* f) {
+    row_vec_fix<T, RAGGED>(row, cols, nfull, v, w);
+    Vec<T, 16>::unpack(w, f);
+}
+
+// acc += sum of the products of two vectors' elements, in element order.  bf16: one packed
+// two-element dot product (fp32 accumulate) per word; fp32: one fused multiply-add per element.
+template <typename T>
+__device__ __forceinline__ float dot_acc(const unsigned* a, const unsigned* b, float acc) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) acc = __builtin_fmaf(__uint_as_float(a[i]), __uint_as_float(b[i]), acc);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, a[i]), __builtin_bit_cast(v2bf, b[i]), acc, false);
+    }
+    return acc;
 }
 
 template <int VB>
@@ -428,42 +459,52 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
 // Memory-bound: every weight is read exactly once.  One wave computes R output columns (R weight
 // rows): per chunk of 4 * 64 vectors of the row it issues all R * 4 weight loads (non-temporal:
 // streamed, no reuse) and the 4 loads of its slice of h before the first multiply, accumulates in
-// fp32 with fused multiply-adds in a fixed order, and reduces across the wave.  No MFMA: at batch 1
-// there is no reuse to feed a matrix core.
+// fp32 in a fixed order, and reduces across the wave.  No MFMA: at batch 1 there is no reuse to
+// feed a matrix core.  Row-shape classes RS (from cols alone): 0 = cols is a whole number of
+// chunks (no bounds handling at all), 1 = a whole number of vectors, 2 = ragged.
 constexpr int kGemvChunk = 4;   // vectors per lane per chunk
 
-template <typename T, int R, bool RAGGED, bool AL>
+template <typename T, int RS, bool AL, bool NT>
+__device__ __forceinline__ void gemv_issue(const T* row, int nfull, int v, unsigned* w) {
+    constexpr int NV = Vec<T, 16>::NV;
+    if constexpr (RS == 0) load_vec<T, 16, AL, NT>(row + (size_t)v * NV, w);
+    else row_vec_issue<T, AL, NT>(row, nfull, v, w);
+}
+template <typename T, int RS>
+__device__ __forceinline__ void gemv_fix(const T* row, int cols, int nfull, int v, unsigned* w) {
+    if constexpr (RS != 0) row_vec_fix<T, RS == 2>(row, cols, nfull, v, w);
+}
+
+template <typename T, int R, int RS, bool AL>
 __device__ __forceinline__ void gemv_body(const T* W, const T* h, T* y, int n, int cols, int j0, int lane) {
     constexpr int NV = Vec<T, 16>::NV;
     const int nfull = cols / NV;
     const int nvec = (cols + NV - 1) / NV;
     float acc[R];
+    const T* wrow[R];
 #pragma unroll
-    for (int r = 0; r < R; r++) acc[r] = 0.f;
+    for (int r = 0; r < R; r++) {
+        acc[r] = 0.f;
+        wrow[r] = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * cols;   // a ragged last group re-reads the last row
+    }
     for (int v0 = 0; v0 < nvec; v0 += 64 * kGemvChunk) {
         unsigned ww[R][kGemvChunk][4], wh[kGemvChunk][4];
-        const T* wrow[R];
-#pragma unroll
-        for (int r = 0; r < R; r++) wrow[r] = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * cols;   // a ragged last group re-reads the last row
-        if (!RAGGED || nfull > 0) {
+        if (RS != 2 || nfull > 0) {
 #pragma unroll
             for (int r = 0; r < R; r++)
 #pragma unroll
-                for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL, true>(wrow[r], nfull, v0 + u * 64 + lane, ww[r][u]);
+                for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, true>(wrow[r], nfull, v0 + u * 64 + lane, ww[r][u]);
 #pragma unroll
-            for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(h, nfull, v0 + u * 64 + lane, wh[u]);
+            for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, false>(h, nfull, v0 + u * 64 + lane, wh[u]);
         }
-        float fh[kGemvChunk][NV];
 #pragma unroll
-        for (int u = 0; u < kGemvChunk; u++) row_vec_finish<T, RAGGED>(h, cols, nfull, v0 + u * 64 + lane, wh[u], fh[u]);
+        for (int u = 0; u < kGemvChunk; u++) gemv_fix<T, RS>(h, cols, nfull, v0 + u * 64 + lane, wh[u]);
 #pragma unroll
         for (int r = 0; r < R; r++)
 #pragma unroll
             for (int u = 0; u < kGemvChunk; u++) {
-                float fw[NV];
-                row_vec_finish<T, RAGGED>(wrow[r], cols, nfull, v0 + u * 64 + lane, ww[r][u], fw);
-#pragma unroll
-                for (int e = 0; e < NV; e++) acc[r] = __builtin_fmaf(fw[e], fh[u][e], acc[r]);
+                gemv_fix<T, RS>(wrow[r], cols, nfull, v0 + u * 64 + lane, ww[r][u]);
+                acc[r] = dot_acc<T>(ww[r][u], wh[u], acc[r]);
             }
     }
 #pragma unroll
@@ -473,7 +514,7 @@ __device__ __forceinline__ void gemv_body(const T* W, const T* h, T* y, int n, i
     }
 }
 
-template <typename T, int IND, int R, bool RAGGED>
+template <typename T, int IND, int R, int RS>
 __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
     const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
     const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
@@ -482,16 +523,16 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
     const int j0 = (blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * R;
     if (j0 >= p.n) return;   // whole wave leaves together
     // row starts of W stay aligned only if cols is a multiple of the vector
-    const bool al = !RAGGED && aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemv_body<T, R, RAGGED, true>(W, h, y, p.n, p.cols, j0, lane);
-    else gemv_body<T, R, RAGGED, false>(W, h, y, p.n, p.cols, j0, lane);
+    const bool al = RS != 2 && aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemv_body<T, R, RS, true>(W, h, y, p.n, p.cols, j0, lane);
+    else gemv_body<T, R, RS, false>(W, h, y, p.n, p.cols, j0, lane);
 }
 
 // Batched (rows > 1): one wave per output column; the weight chunk stays in registers while the
 // rows of h stream past it, kRowBlock rows at a time.
 constexpr int kRowBlock = 4;
 
-template <typename T, bool RAGGED, bool AL>
+template <typename T, int RS, bool AL>
 __device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int rows, int n, int cols, int j, int lane) {
     constexpr int NV = Vec<T, 16>::NV;
     const int nfull = cols / NV;
@@ -499,32 +540,30 @@ __device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int row
     const T* wrow = W + (size_t)j * cols;
     for (int r0 = 0; r0 < rows; r0 += kRowBlock) {
         float acc[kRowBlock];
+        const T* hrow[kRowBlock];
 #pragma unroll
-        for (int rr = 0; rr < kRowBlock; rr++) acc[rr] = 0.f;
+        for (int rr = 0; rr < kRowBlock; rr++) {
+            acc[rr] = 0.f;
+            hrow[rr] = h + (size_t)((r0 + rr < rows) ? r0 + rr : rows - 1) * cols;
+        }
         for (int v0 = 0; v0 < nvec; v0 += 64 * kGemvChunk) {
             unsigned ww[kGemvChunk][4], wh[kRowBlock][kGemvChunk][4];
-            const T* hrow[kRowBlock];
+            if (RS != 2 || nfull > 0) {
 #pragma unroll
-            for (int rr = 0; rr < kRowBlock; rr++) hrow[rr] = h + (size_t)((r0 + rr < rows) ? r0 + rr : rows - 1) * cols;
-            if (!RAGGED || nfull > 0) {
-#pragma unroll
-                for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(wrow, nfull, v0 + u * 64 + lane, ww[u]);
+                for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, false>(wrow, nfull, v0 + u * 64 + lane, ww[u]);
 #pragma unroll
                 for (int rr = 0; rr < kRowBlock; rr++)
 #pragma unroll
-                    for (int u = 0; u < kGemvChunk; u++) row_vec_issue<T, AL>(hrow[rr], nfull, v0 + u * 64 + lane, wh[rr][u]);
+                    for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, false>(hrow[rr], nfull, v0 + u * 64 + lane, wh[rr][u]);
             }
-            float fw[kGemvChunk][NV];
 #pragma unroll
-            for (int u = 0; u < kGemvChunk; u++) row_vec_finish<T, RAGGED>(wrow, cols, nfull, v0 + u * 64 + lane, ww[u], fw[u]);
+            for (int u = 0; u < kGemvChunk; u++) gemv_fix<T, RS>(wrow, cols, nfull, v0 + u * 64 + lane, ww[u]);
 #pragma unroll
             for (int rr = 0; rr < kRowBlock; rr++)
 #pragma unroll
                 for (int u = 0; u < kGemvChunk; u++) {
-                    float fh[NV];
-                    row_vec_finish<T, RAGGED>(hrow[rr], cols, nfull, v0 + u * 64 + lane, wh[rr][u], fh);
-#pragma unroll
-                    for (int e = 0; e < NV; e++) acc[rr] = __builtin_fmaf(fw[u][e], fh[e], acc[rr]);
+                    gemv_fix<T, RS>(hrow[rr], cols, nfull, v0 + u * 64 + lane, wh[rr][u]);
+                    acc[rr] = dot_acc<T>(ww[u], wh[rr][u], acc[rr]);
                 }
         }
 #pragma unroll
@@ -535,7 +574,7 @@ __device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int row
     }
 }
 
-template <typename T, int IND, bool RAGGED>
+template <typename T, int IND, int RS>
 __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
     const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
     const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
@@ -543,9 +582,9 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
     const int lane = threadIdx.x & 63;
     const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
     if (j >= p.n) return;
-    const bool al = !RAGGED && aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemvb_body<T, RAGGED, true>(W, h, y, p.rows, p.n, p.cols, j, lane);
-    else gemvb_body<T, RAGGED, false>(W, h, y, p.rows, p.n, p.cols, j, lane);
+    const bool al = RS != 2 && aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemvb_body<T, RS, true>(W, h, y, p.rows, p.n, p.cols, j, lane);
+    else gemvb_body<T, RS, false>(W, h, y, p.rows, p.n, p.cols, j, lane);
 }
 
 // ---- batched multi-tensor copy -----------------------------------------------------------------
@@ -681,44 +720,50 @@ bool plan_rms(int ind, int rows, int cols, Launch* out) {
     return out->fn != nullptr;
 }
 
-template <typename T, int R, bool RAGGED>
+template <typename T, int R, int RS>
 const void* gemv_by_ind(int ind) {
     switch (ind) {
-    case 0: return PG_FN(k_gemv<T, 0, R, RAGGED>);
-    case 1: return PG_FN(k_gemv<T, 1, R, RAGGED>);
-    case 2: return PG_FN(k_gemv<T, 2, R, RAGGED>);
-    case 3: return PG_FN(k_gemv<T, 3, R, RAGGED>);
+    case 0: return PG_FN(k_gemv<T, 0, R, RS>);
+    case 1: return PG_FN(k_gemv<T, 1, R, RS>);
+    case 2: return PG_FN(k_gemv<T, 2, R, RS>);
+    case 3: return PG_FN(k_gemv<T, 3, R, RS>);
     default: return nullptr;
     }
 }
-template <typename T, bool RAGGED>
+template <typename T, int RS>
 const void* gemvb_by_ind(int ind) {
     switch (ind) {
-    case 0: return PG_FN(k_gemv_batched<T, 0, RAGGED>);
-    case 1: return PG_FN(k_gemv_batched<T, 1, RAGGED>);
-    case 2: return PG_FN(k_gemv_batched<T, 2, RAGGED>);
-    case 3: return PG_FN(k_gemv_batched<T, 3, RAGGED>);
+    case 0: return PG_FN(k_gemv_batched<T, 0, RS>);
+    case 1: return PG_FN(k_gemv_batched<T, 1, RS>);
+    case 2: return PG_FN(k_gemv_batched<T, 2, RS>);
+    case 3: return PG_FN(k_gemv_batched<T, 3, RS>);
     default: return nullptr;
     }
+}
+
+template <typename T, int RS>
+bool plan_gemv_rs(int ind, int rows, int n, Launch* out) {
+    out->block = dim3(kBlock);
+    if (rows == 1 && n >= 1024) {
+        // two weight rows per wave once there are enough rows to fill the chip with half the waves
+        out->fn = gemv_by_ind<T, 2, RS>(ind);
+        out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
+    } else if (rows == 1) {
+        out->fn = gemv_by_ind<T, 1, RS>(ind);
+        out->grid = dim3(blocks_for(n, kBlock / 64));
+    } else {
+        out->fn = gemvb_by_ind<T, RS>(ind);
+        out->grid = dim3(blocks_for(n, kBlock / 64));
+    }
+    return out->fn != nullptr;
 }
 
 template <typename T>
 bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     constexpr int NV = 16 / (int)sizeof(T);
-    const bool ragged = (cols % NV) != 0;
-    out->block = dim3(kBlock);
-    if (rows == 1 && n >= 1024) {
-        // two weight rows per wave once there are enough rows to fill the chip with half the waves
-        out->fn = ragged ? gemv_by_ind<T, 2, true>(ind) : gemv_by_ind<T, 2, false>(ind);
-        out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
-    } else if (rows == 1) {
-        out->fn = ragged ? gemv_by_ind<T, 1, true>(ind) : gemv_by_ind<T, 1, false>(ind);
-        out->grid = dim3(blocks_for(n, kBlock / 64));
-    } else {
-        out->fn = ragged ? gemvb_by_ind<T, true>(ind) : gemvb_by_ind<T, false>(ind);
-        out->grid = dim3(blocks_for(n, kBlock / 64));
-    }
-    return out->fn != nullptr;
+    if (cols % (64 * kGemvChunk * NV) == 0) return plan_gemv_rs<T, 0>(ind, rows, n, out);
+    if (cols % NV == 0) return plan_gemv_rs<T, 1>(ind, rows, n, out);
+    return plan_gemv_rs<T, 2>(ind, rows, n, out);
 }
 
 template <typename T, bool VEC, int U, typename IdxT>

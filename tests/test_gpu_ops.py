@@ -70,6 +70,22 @@ def test_elementwise(op, dtype, n, m, offs):
     assert_close(got, want, dtype, f"{op} {dtype} n={n}")
 
 
+def test_bf16_rounding_edges_on_the_gpu():
+    """The store's fp32 -> bf16 conversion: ties to even, subnormal results, overflow to infinity,
+    signed zeros -- bit for bit as the oracle rounds."""
+    a = np.array([0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x0080, 0x0001, 0x0003, 0x7F7F, 0xFF7F, 0x0000, 0x8000, 0x0040,
+                  0x4000, 0x3F81, 0x0100, 0x00FF], np.uint16)
+    b = np.array([0x3B80, 0x3C00, 0x3B81, 0x3C40, 0x3F00, 0x3F00, 0x3F00, 0x7F7F, 0xFF7F, 0x8000, 0x8000, 0x3E80,
+                  0x3F81, 0x3F81, 0x3F40, 0x3F00], np.uint16)
+    n = a.size
+    for op in ("add", "mul"):
+        k = KernelSpec(op, "bf16", 0, (Ref(EXT, 0), Ref(EXT, 1)), n, m=n)
+        spec = ChainSpec("e", [k], [TensorSpec("bf16", n)] * 2, [TensorSpec("bf16", n)], [], [0])
+        got = run_single(spec, [a, b], [], None, "edges " + op)
+        want = oracle.run_chain(spec, [], [a, b])[0]
+        assert same_bits(got, want), (op, [hex(x) for x in got], [hex(x) for x in want])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_gelu_special_values(dtype):
     vals = np.array([0.0, -0.0, 10.0, 12.5, 40.0, 1000.0, -40.0, -100.0, -1e4, 1.0, -1.0, -0.75, 5.0, -5.0, -8.0, 3e-20], np.float32)
