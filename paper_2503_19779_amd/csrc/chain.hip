@@ -330,9 +330,16 @@ pg_status make_records(pg_chain* c) {
 }
 
 // ---- launches ----------------------------------------------------------------------------------------
-inline hipError_t launch(const pgk::Launch& L, ArgBlock* a, hipStream_t s) {
-    void* args[1] = {a};
-    return hipLaunchKernel(L.fn, L.grid, L.block, args, 0, s);
+// The leanest launch the runtime offers: a module function resolved once, the argument block handed
+// over as one packed buffer (no per-launch symbol lookup, no per-argument marshalling).
+inline hipError_t launch(pgk::Launch& L, ArgBlock* a, hipStream_t s) {
+    if (!L.mod_fn) {
+        hipError_t e = hipGetFuncBySymbol(&L.mod_fn, L.fn);
+        if (e != hipSuccess) return e;
+    }
+    size_t sz = L.arg_bytes;
+    void* extra[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
+    return hipModuleLaunchKernel(L.mod_fn, L.grid.x, 1, 1, L.block.x, 1, 1, 0, s, nullptr, extra);
 }
 
 pg_status check_call(const pg_chain* c, const void* const* ext, void* stream, bool need_capture) {

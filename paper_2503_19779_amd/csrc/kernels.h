@@ -71,7 +71,9 @@ struct TableArgs {
 };
 
 struct Launch {
-    const void* fn = nullptr;    // host-side kernel handle for hipLaunchKernel
+    const void* fn = nullptr;        // host-side kernel handle
+    hipFunction_t mod_fn = nullptr;  // the same kernel as a module function, resolved on first launch
+    unsigned arg_bytes = 0;          // size of the kernel's argument block
     dim3 grid{1, 1, 1};
     dim3 block{1, 1, 1};
 };

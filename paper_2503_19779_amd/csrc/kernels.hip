@@ -814,6 +814,14 @@ bool plan_t(int op, int ind, const Shape& s, Launch* out) {
 }  // namespace
 
 bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out) {
+    switch (op) {
+    case kAdd: case kMul: case kGelu: out->arg_bytes = sizeof(EwArgs); break;
+    case kRmsNorm: out->arg_bytes = sizeof(RmsArgs); break;
+    case kGemv: out->arg_bytes = sizeof(GemvArgs); break;
+    case kScaleBiasRelu: out->arg_bytes = sizeof(SbrArgs); break;
+    default: return false;
+    }
+    out->mod_fn = nullptr;
     if (dtype == kF32) return plan_t<float>(op, ind_mask, shape, out);
     if (dtype == kBF16) return plan_t<bf16_t>(op, ind_mask, shape, out);
     return false;
