@@ -36,6 +36,7 @@ def main() -> int:
     ap.add_argument("--no-copy-bench", action="store_true", help="skip the copy-kernel bandwidth leg (config 3 sizes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); run it with --gpus 1", file=sys.stderr)
@@ -69,7 +70,7 @@ def main() -> int:
     t0 = time.time()
     chain.capture(stream)
     capture_s = time.time() - t0
-    cost = chain.profile(x_dev[0], stream, iters=20, inner=3)
+    cost = chain.profile(x_dev[0], stream, iters=args.profile_iters, inner=3)
     sel = pg.select(cost)
     log(f"[bench] captured in {capture_s * 1e3:.1f} ms; cost table (us) {cost.tolist()} -> selected mode {sel.tolist()}")
 
@@ -90,21 +91,36 @@ def main() -> int:
     chain.set_table_refresh(pg.TABLE_KERNARG)
     log(f"[bench] graph_indirect with a pinned-memcpy table refresh: {us_ind_memcpy:.1f} us/iteration")
 
-    # ------------------------------------------------------------------ per-kernel GPU time (events on the kernels' own timestamps)
+    # ------------------------------------------------------------------ the dominant kernel alone: GEMV 2048x2048, HIP events on the launch stream
+    # A graph of the chain's 120 GEMV launches and nothing else (same kernel, same launch shape, the
+    # chain's own 120 weight matrices, input vector fixed): events around R replays give the time per
+    # launch.  It includes the dispatch gap between two dependent launches, so it is an upper bound of
+    # the kernel's own duration (the rocprofv3 kernel trace gives the latter).
+    from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, INT, WEIGHT
     n_k = len(spec.kernels)
-    reps = 5
-    chain.time_kernels(x_dev[0], stream)
-    dur = np.stack([chain.time_kernels(x_dev[r % n_sets], stream) for r in range(reps)])     # [reps, n_k] us
-    ops = np.array([k.op for k in spec.kernels])
-    busy_us = float(dur.sum(axis=1).mean())
-    per_op = {op: {"count": int((ops == op).sum()), "mean_us": float(dur[:, ops == op].mean())} for op in sorted(set(ops.tolist()))}
-    gemv_us = per_op["gemv"]["mean_us"]
-    gemv_bytes = 2048 * 2048 * 2 + 2048 * 2 + 2048 * 2       # weight row-major bf16 + input vector + output vector
-    log(f"[bench] GPU-busy time per iteration {busy_us:.1f} us; per op {per_op}")
-    idle = {m: max(0.0, 1.0 - busy_us / us[m]) for m in us}
+    n_gemv = sum(1 for k in spec.kernels if k.op == "gemv")
+    H = spec.meta["hidden"]
+    gspec = ChainSpec("gemv_only", [KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s), Ref(WEIGHT, n_gemv)), H, rows=1, cols=H) for s in range(n_gemv)],
+                      [], [TensorSpec("bf16", H)], list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H)], [0])
+    gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0]], dev)
+    gchain.capture(stream)
+    reps = 50
+    for _ in range(5):
+        gchain.replay_copy([], stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        gchain.replay_copy([], stream)        # no external input: this is the graph launch alone
+    e1.record(stream)
+    e1.synchronize()
+    gemv_us = e0.elapsed_time(e1) * 1e3 / (reps * n_gemv)
+    gchain.close()
+    gemv_bytes = H * H * 2 + H * 2 + H * 2       # bf16 weight matrix + input vector + output vector
+    log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s")
     roofline = {"kernel": "k_gemv<bf16> 2048x2048, batch 1", "bound": "hbm", "achieved": gemv_bytes / gemv_us / 1e3,
                 "peak": HBM_PEAK, "unit": "GB/s", "frac": gemv_bytes / gemv_us / 1e3 / HBM_PEAK,
-                "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": int((ops == "gemv").sum()) * reps,
+                "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": reps * n_gemv,
+                "how": "HIP events on the launch stream around 50 replays of a graph of the chain's 120 GEMV launches; per-launch time includes the inter-kernel dispatch gap",
                 "traffic": None}
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
@@ -134,6 +150,15 @@ def main() -> int:
         for name, mode in (("eager", pg.EAGER), ("graph_copy", pg.GRAPH_COPY), ("graph_indirect", pg.GRAPH_INDIRECT)):
             chain3.time_loop(mode, sets3, 3, stream)
             us3[name] = chain3.time_loop(mode, sets3, 20, stream)
+        # a plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick the
+        # hardware-counter byte counts of a profiled run are scaled by
+        cal_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        cal_dst = torch.empty_like(cal_src)
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                cal_dst.copy_(cal_src)
+        stream.synchronize()
+        del cal_src, cal_dst
         copy["refresh_stress_chain_us_per_iter"] = us3
         log(f"[bench] refresh-stress chain (256 kernels): {us3}")
         chain3.close()
@@ -176,7 +201,7 @@ def main() -> int:
         "speedup_vs_eager": {m: us["eager"] / us[m] for m in us},
         "graph_indirect_memcpy_table_us": us_ind_memcpy,
         "selection": {"cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()], "mode": sel.tolist()},
-        "gpu_busy_us_per_iteration": busy_us, "idle_gap_fraction": idle, "kernel_time_us": per_op,
+        "idle_gap_fraction": None,   # needs per-kernel durations: taken from the rocprofv3 kernel trace, reported with the profile summaries
         "chain_level_GBps": chain_level, "chain_level_hbm_frac": {m: chain_level[m] / HBM_PEAK for m in us},
         "bytes_refreshed_per_replay": {"graph_copy": chain.stats()["copy_bytes_per_replay"], "graph_indirect": chain.stats()["table_bytes_per_replay"]},
         "capture_ms": capture_s * 1e3,

@@ -1,0 +1,158 @@
+"""Timing report for the benchmark chains other than the one bench.py times:
+
+    python -m paper_2503_19779_amd.configs_report --config 1 3 4 5
+
+Per chain: capture, slow-path profile -> cost table -> selection, then microseconds per iteration
+for eager, graph-copy, graph-indirect and the selected mixture (back-to-back iterations on one
+stream, one synchronisation at the end, inputs rotating over distinct allocations), launches per
+second, bytes per iteration against the 8 TB/s HBM figure.  One JSON line per config on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+HBM_PEAK = 8000.0  # GB/s
+
+
+def chain_bytes(spec) -> int:
+    """Algorithmic bytes one iteration moves: every operand read once, every output written once."""
+    eb = {"f32": 4, "bf16": 2}
+    total = 0
+    for k in spec.kernels:
+        e = eb[k.dtype]
+        if k.op in ("add", "mul"):
+            total += (2 * k.n + min(k.m or k.n, k.n)) * e
+        elif k.op == "gelu":
+            total += 2 * k.n * e
+        elif k.op == "rmsnorm":
+            total += (2 * k.rows * k.cols + k.cols) * e
+        elif k.op == "gemv":
+            total += (k.n * k.cols + k.rows * k.cols + k.rows * k.n) * e
+        else:
+            total += (2 * k.n + 2 * k.channels) * e
+    return total
+
+
+def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile_iters=10):
+    chain = pg.Chain(spec, w_dev)
+    t0 = time.time()
+    chain.capture(stream)
+    cap_ms = (time.time() - t0) * 1e3
+    sets = make_sets()
+    cost = chain.profile(sets[0], stream, iters=profile_iters, inner=2)
+    sel = pg.select(cost)
+    us = {}
+    for name, mode, modes in (("eager", pg.EAGER, None), ("graph_copy", pg.GRAPH_COPY, None),
+                              ("graph_indirect", pg.GRAPH_INDIRECT, None), ("selected", pg.SELECTED, sel)):
+        chain.time_loop(mode, sets, warmup, stream, modes)
+        us[name] = chain.time_loop(mode, sets, iters, stream, modes)
+    st = chain.stats()
+    return chain, {"us_per_iteration": us, "capture_ms": cap_ms,
+                   "cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()],
+                   "selected_mode": sel.tolist(), "kernels": st["n_kernels"], "segments": st["n_segments"],
+                   "bytes_refreshed_per_replay": {"graph_copy": st["copy_bytes_per_replay"], "graph_indirect": st["table_bytes_per_replay"]},
+                   "launches_per_s": {m: st["n_kernels"] / v * 1e6 for m, v in us.items()}}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, nargs="+", default=[1, 3, 4, 5])
+    ap.add_argument("--iters", type=int, default=100)
+    args = ap.parse_args()
+    import torch
+    import paper_2503_19779_amd as pg
+    from paper_2503_19779_amd.binding import to_device
+    from pg_workloads import (elementwise_chain, refresh_stress_chain, large_tensor_chain, decode_buckets, bucket_sequence,
+                              make_weights, make_inputs)
+    stream = torch.cuda.Stream()
+
+    def host_sets(spec, n):
+        return lambda: [[to_device(x) for x in make_inputs(spec, t)] for t in range(n)]
+
+    def device_sets(spec, n):
+        def make():
+            g = torch.Generator(device="cuda")
+            g.manual_seed(spec.seed)
+            dt = {"f32": torch.float32, "bf16": torch.bfloat16}
+            return [[torch.randn(t.numel, device="cuda", generator=g, dtype=torch.float32).to(dt[t.dtype]) for t in spec.ext] for _ in range(n)]
+        return make
+
+    for cfg in args.config:
+        if cfg == 1:
+            spec = elementwise_chain()
+            chain, r = time_chain(pg, torch, spec, [], host_sets(spec, 3), args.iters, 10, stream)
+        elif cfg == 3:
+            spec = refresh_stress_chain()
+            w = [to_device(a) for a in make_weights(spec)]
+            chain, r = time_chain(pg, torch, spec, w, device_sets(spec, 2), min(args.iters, 30), 3, stream)
+            sets = device_sets(spec, 2)()
+            cu = np.array([chain.time_refresh_copy(sets[i % 2], stream) for i in range(23)][3:])
+            r["copy_kernel"] = {"us": float(cu.mean()), "GBps": 2 * spec.ext_bytes() / float(cu.mean()) / 1e3,
+                                "hbm_frac": 2 * spec.ext_bytes() / float(cu.mean()) / 1e3 / HBM_PEAK}
+        elif cfg == 4:
+            spec = large_tensor_chain()
+            w = [to_device(a) for a in make_weights(spec)]
+            chain, r = time_chain(pg, torch, spec, w, device_sets(spec, 3), min(args.iters, 30), 3, stream)
+            x = device_sets(spec, 1)()[0]
+            d = chain.time_kernels(x, stream)
+            d = chain.time_kernels(x, stream)
+            r["kernel_us"] = float(np.median(d))
+            r["kernel_GBps"] = 2 * spec.ext[0].nbytes / float(np.median(d)) / 1e3
+        elif cfg == 5:
+            specs = decode_buckets()
+            w = [to_device(a) for a in make_weights(specs[0])]
+            per_bucket, chains, sets = [], [], []
+            for spec in specs:
+                chain, r = time_chain(pg, torch, spec, w, device_sets(spec, 2), 20, 3, stream, profile_iters=5)
+                per_bucket.append({"batch": spec.meta["batch"], **r,
+                                   "algorithmic_GBps": {m: chain_bytes(spec) / v / 1e3 for m, v in r["us_per_iteration"].items()}})
+                chains.append(chain)
+                sets.append(device_sets(spec, 2)())
+                log(f"[configs] bucket B={spec.meta['batch']}: {r['us_per_iteration']} selected {r['selected_mode']}")
+            seq = bucket_sequence(len(specs), 1000)
+            out = {}
+            for name, mode in (("eager", pg.EAGER), ("graph_copy", pg.GRAPH_COPY), ("graph_indirect", pg.GRAPH_INDIRECT), ("selected", pg.SELECTED)):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for it, b in enumerate(seq.tolist()):
+                    ch, x = chains[b], sets[b][it % 2]
+                    if mode == pg.EAGER:
+                        ch.eager(x, stream)
+                    elif mode == pg.GRAPH_COPY:
+                        ch.replay_copy(x, stream)
+                    elif mode == pg.GRAPH_INDIRECT:
+                        ch.replay_indirect(x, stream)
+                    else:
+                        ch.run_selected(per_bucket[b]["selected_mode"], x, stream)
+                torch.cuda.synchronize()
+                out[name] = (time.perf_counter() - t0) / len(seq) * 1e6
+            print(json.dumps({"config": 5, "workload": "decode chain, 8 batch-size buckets 1..128, random bucket sequence of 1000 iterations",
+                              "us_per_iteration_over_sequence": out, "per_bucket": per_bucket}), flush=True)
+            for ch in chains:
+                ch.close()
+            continue
+        else:
+            log(f"config {cfg}: use bench.py for the decode chain")
+            continue
+        b = chain_bytes(spec)
+        r.update({"config": cfg, "workload": spec.name, "algorithmic_bytes_per_iteration": b,
+                  "algorithmic_GBps": {m: b / v / 1e3 for m, v in r["us_per_iteration"].items()},
+                  "hbm_floor_us": b / HBM_PEAK / 1e3})
+        log(f"[configs] config {cfg}: {r['us_per_iteration']} selected {r['selected_mode']}")
+        print(json.dumps(r), flush=True)
+        chain.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
