@@ -50,7 +50,7 @@ struct SbrArgs {
 // Batched multi-tensor copy: the destination side is static and lives in device memory, the
 // source pointers change every replay and travel in the argument block.
 constexpr int kCopyMaxSrc = 448;           // 448 * 8 B + header < 4 KB of kernel arguments
-constexpr unsigned kCopyChunkBytes = 65536;  // bytes of one tensor handled by one workgroup
+constexpr unsigned kCopyChunkBytes = 8192;   // bytes of one tensor handled by one workgroup: 256 lanes x 2 x 16 B
 struct CopyTensor { void* dst; unsigned long long bytes; };
 struct CopyChunk { unsigned tensor; unsigned len; unsigned long long off; };
 struct CopyArgs {

@@ -181,7 +181,7 @@ def test_scale_bias_relu_with_external_scale_and_bias():
 def test_copy_kernel_sizes_and_misalignments():
     """Placeholder == source, byte for byte, for sizes around every boundary of the kernel (vector
     width, chunk size) and every element-aligned source misalignment."""
-    sizes = [2, 4, 14, 16, 18, 30, 1022, 1024, 1026, 65534, 65536, 65538, 131072 + 6, 16 * 2 ** 20, 16 * 2 ** 20 + 2]
+    sizes = [2, 4, 14, 16, 18, 30, 1022, 1024, 1026, 8190, 8192, 8194, 16384 + 6, 65534, 65536, 65538, 16 * 2 ** 20, 16 * 2 ** 20 + 2]
     ext = [TensorSpec("bf16", s // 2) for s in sizes]
     # one kernel that reads the first external so that the chain is valid; the copy list covers all of them
     ks = [KernelSpec("gelu", "bf16", 0, (Ref(EXT, 0),), 1)]

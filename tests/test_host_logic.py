@@ -100,7 +100,7 @@ def test_bytes_accounting_and_layout(make):
     assert st["copy_bytes_per_replay"] == spec.ext_bytes()            # payload of a copy refresh
     assert st["table_bytes_per_replay"] == 8 * len(spec.ext)          # 8 bytes per indirected parameter
     assert st["n_ext_reading_kernels"] == spec.n_ext_reading_kernels()
-    assert st["copy_chunks"] == sum(-(-t.nbytes // 65536) for t in spec.ext)
+    assert st["copy_chunks"] == sum(-(-t.nbytes // 8192) for t in spec.ext)
     spans = [ch.raw_layout("ext", i) for i in range(len(spec.ext))] + [ch.raw_layout("int", i) for i in range(len(spec.ints))]
     spans.append(ch.raw_layout("table"))
     for (off, nb), t in zip(spans, list(spec.ext) + list(spec.ints)):
