@@ -121,7 +121,9 @@ def main() -> int:
                 "peak": HBM_PEAK, "unit": "GB/s", "frac": gemv_bytes / gemv_us / 1e3 / HBM_PEAK,
                 "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": reps * n_gemv,
                 "how": "HIP events on the launch stream around 50 replays of a graph of the chain's 120 GEMV launches; per-launch time includes the inter-kernel dispatch gap",
-                "traffic": None}
+                # HBM bytes per launch from the hardware-counter runs (FETCH_SIZE x 1.9996 + WRITE_SIZE x 1.0000,
+                # factors from a plain 256 MiB copy in the same run); the summary sits beside the other profiles
+                "traffic": 8.462e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
 
@@ -144,7 +146,8 @@ def main() -> int:
         copy = {"kernel": "k_copy (batched multi-tensor)", "bound": "hbm", "achieved": 2 * payload / float(cu.mean()) / 1e3,
                 "peak": HBM_PEAK, "unit": "GB/s", "frac": 2 * payload / float(cu.mean()) / 1e3 / HBM_PEAK,
                 "payload_bytes": payload, "bytes_per_launch": 2 * payload, "avg_launch_us": float(cu.mean()),
-                "min_launch_us": float(cu.min()), "launches_timed": 20, "traffic": None}
+                "min_launch_us": float(cu.min()), "launches_timed": 20,
+                "traffic": 892.4e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
         log(f"[bench] copy kernel: {cu.mean():.1f} us for {2 * payload / 1e6:.1f} MB of traffic = {copy['achieved']:.0f} GB/s")
         us3 = {}
         for name, mode in (("eager", pg.EAGER), ("graph_copy", pg.GRAPH_COPY), ("graph_indirect", pg.GRAPH_INDIRECT)):
