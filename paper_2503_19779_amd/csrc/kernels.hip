@@ -587,6 +587,124 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
     else gemvb_body<T, RS, false>(W, h, y, p.rows, p.n, p.cols, j, lane);
 }
 
+// Batched bf16 with whole 16-byte vectors per row: y[rows, n] = h[rows, cols] * W[n, cols]^T is a
+// dense contraction once rows > 1, so it goes to the matrix cores (v_mfma_f32_16x16x32_bf16, fp32
+// accumulate).  Still weight-streaming bound up to rows ~ 128: every weight is read once from HBM.
+//   - one workgroup per 16 output columns; its 4 waves split K: of every 8 consecutive 32-wide
+//     K-steps wave w takes steps 2w and 2w+1 (128 contiguous bytes of each weight row), 16 steps per
+//     2048 columns, one 16-byte fragment per lane each, all issued up front;
+//   - both operands are read straight from global memory as 16-byte vectors along K (A = h rows,
+//     B = W rows), no transposes and no LDS on the way in: lane l holds row/column (l & 15) and the
+//     8 consecutive k's of chunk (l >> 4) of each step;
+//   - the rows of h pass in pairs of 16-row tiles (32 fragment loads in flight) against the weight
+//     fragments, which stay in registers when cols <= 2048 (SINGLE) and are re-read per pair (from
+//     cache) otherwise; rows beyond the batch re-read the last row and are never stored;
+//   - per pair the 4 waves' partial tiles are summed through LDS in a fixed order; lane l of a tile
+//     holds column (l & 15), rows 4 * (l >> 4) .. + 3.
+// The pair loop is deliberately not unrolled: a kernel this short runs its code once, so code size
+// is instruction-fetch time.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kMmSteps = 16;      // K-steps per wave per super-chunk (4 waves x 16 steps x 32 = 2048 columns)
+
+template <bool FULL, bool AL, bool NT>
+__device__ __forceinline__ void mm_load_w(const bf16_t* wrow, int cols, int s0, int wave, int kq, unsigned (*wf)[4], int* koff, bool* ok) {
+#pragma unroll
+    for (int i = 0; i < kMmSteps; i++) {
+        const int k0 = (s0 + (i >> 1) * 8 + wave * 2 + (i & 1)) * 32 + kq * 8;
+        ok[i] = FULL || k0 < cols;                      // cols is a multiple of 8: a chunk is all in or all out
+        koff[i] = ok[i] ? k0 : 0;
+        load_vec<bf16_t, 16, AL, NT>(wrow + koff[i], wf[i]);
+    }
+}
+
+template <bool FULL, bool AL>
+__device__ __forceinline__ void mm_pair(const bf16_t* h, int rows, int cols, int r0, int rc, const unsigned (*wf)[4], const int* koff,
+                                        const bool* ok, f32x4* acc) {
+    unsigned hf[2][kMmSteps][4];
+    const bf16_t* hrow[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; tt++) {
+        const int r = r0 + tt * 16 + rc;
+        hrow[tt] = h + (size_t)(r < rows ? r : rows - 1) * cols;
+    }
+#pragma unroll
+    for (int i = 0; i < kMmSteps; i++)      // in the order the MFMAs consume them
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++) load_vec<bf16_t, 16, AL, false>(hrow[tt] + koff[i], hf[tt][i]);
+    // keep all 32 fragment loads ahead of the first MFMA: left alone, the scheduler sinks them next to
+    // their uses to save registers and the loop then pays one cache latency per fragment
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kMmSteps; i++) {
+        v4u b;
+        b.x = wf[i][0]; b.y = wf[i][1]; b.z = wf[i][2]; b.w = wf[i][3];
+        if (!FULL && !ok[i]) b = v4u{0u, 0u, 0u, 0u};      // a zero weight fragment cancels whatever A holds
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++) {
+            v4u a;
+            a.x = hf[tt][i][0]; a.y = hf[tt][i][1]; a.z = hf[tt][i][2]; a.w = hf[tt][i][3];
+            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[tt], 0, 0, 0);
+        }
+    }
+}
+
+template <bool FULL, bool SINGLE, bool AL>
+__device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols,
+                                               float* red /* LDS: [4 waves][2 tiles][64 lanes][4] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rc = lane & 15, kq = lane >> 4;
+    const int j0 = blockIdx.x * 16;
+    const bf16_t* wrow = W + (size_t)((j0 + rc < n) ? j0 + rc : n - 1) * cols;
+    unsigned wf[kMmSteps][4];
+    int koff[kMmSteps];
+    bool ok[kMmSteps];
+    if constexpr (SINGLE) mm_load_w<FULL, AL, true>(wrow, cols, 0, wave, kq, wf, koff, ok);   // streamed once: non-temporal
+#pragma unroll 1
+    for (int r0 = 0; r0 < rows; r0 += 32) {
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        if constexpr (SINGLE) {
+            mm_pair<FULL, AL>(h, rows, cols, r0, rc, wf, koff, ok, acc);
+        } else {
+#pragma unroll 1
+            for (int s0 = 0; s0 * 32 < cols; s0 += 4 * kMmSteps) {
+                mm_load_w<FULL, AL, false>(wrow, cols, s0, wave, kq, wf, koff, ok);
+                mm_pair<FULL, AL>(h, rows, cols, r0, rc, wf, koff, ok, acc);
+            }
+        }
+        // sum the 4 waves' partial tiles in a fixed order and store
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++) {
+            float* dst = red + ((size_t)(wave * 2 + tt) * 64 + lane) * 4;
+            dst[0] = acc[tt].x; dst[1] = acc[tt].y; dst[2] = acc[tt].z; dst[3] = acc[tt].w;
+        }
+        __syncthreads();
+        if (wave < 2) {      // wave 0 finishes tile 0 of the pair, wave 1 tile 1
+            const int tt = wave;
+            const int j = j0 + rc;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float p0 = red[((size_t)(0 * 2 + tt) * 64 + lane) * 4 + e], p1 = red[((size_t)(1 * 2 + tt) * 64 + lane) * 4 + e];
+                const float p2 = red[((size_t)(2 * 2 + tt) * 64 + lane) * 4 + e], p3 = red[((size_t)(3 * 2 + tt) * 64 + lane) * 4 + e];
+                const int r = r0 + tt * 16 + kq * 4 + e;
+                if (r < rows && j < n) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
+            }
+        }
+        __syncthreads();      // `red` is free again
+    }
+}
+
+template <int IND, bool FULL, bool SINGLE>
+__global__ __launch_bounds__(kBlock) void k_gemm_mfma_bf16(GemvArgs p) {
+    const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
+    const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
+    bf16_t* y = static_cast<bf16_t*>(p.out);
+    __shared__ float red[4 * 2 * 64 * 4];
+    const bool al = aligned_to(W, 16) && aligned_to(h, 16);   // rows keep the alignment: cols is a multiple of 8
+    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, red);
+    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, red);
+}
+
 // ---- batched multi-tensor copy -----------------------------------------------------------------
 // One workgroup per chunk (<= kCopyChunkBytes of one tensor): every lane issues its two 128-bit
 // non-temporal loads, then its two stores, and the workgroup is done -- measured on the log-uniform
@@ -761,9 +879,32 @@ bool plan_gemv_rs(int ind, int rows, int n, Launch* out) {
     return out->fn != nullptr;
 }
 
+template <bool FULL, bool SINGLE>
+const void* gemm_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_gemm_mfma_bf16<0, FULL, SINGLE>);
+    case 1: return PG_FN(k_gemm_mfma_bf16<1, FULL, SINGLE>);
+    case 2: return PG_FN(k_gemm_mfma_bf16<2, FULL, SINGLE>);
+    case 3: return PG_FN(k_gemm_mfma_bf16<3, FULL, SINGLE>);
+    default: return nullptr;
+    }
+}
+
 template <typename T>
 bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     constexpr int NV = 16 / (int)sizeof(T);
+    if constexpr (sizeof(T) == 2) {
+        if (rows > 1 && cols % 8 == 0) {   // a dense contraction: matrix cores
+            out->block = dim3(kBlock);
+            out->grid = dim3(blocks_for(n, 16));
+            constexpr int kSuper = 32 * 4 * kMmSteps;   // columns one pass of the 4 waves covers
+            if (cols == kSuper) out->fn = gemm_by_ind<true, true>(ind);
+            else if (cols < kSuper) out->fn = gemm_by_ind<false, true>(ind);
+            else if (cols % kSuper == 0) out->fn = gemm_by_ind<true, false>(ind);
+            else out->fn = gemm_by_ind<false, false>(ind);
+            return out->fn != nullptr;
+        }
+    }
     if (cols % (64 * kGemvChunk * NV) == 0) return plan_gemv_rs<T, 0>(ind, rows, n, out);
     if (cols % NV == 0) return plan_gemv_rs<T, 1>(ind, rows, n, out);
     return plan_gemv_rs<T, 2>(ind, rows, n, out);
