@@ -591,85 +591,118 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
 // dense contraction once rows > 1, so it goes to the matrix cores (v_mfma_f32_16x16x32_bf16, fp32
 // accumulate).  Still weight-streaming bound up to rows ~ 128: every weight is read once from HBM.
 //   - one workgroup per 16 output columns; its 4 waves split K: of every 8 consecutive 32-wide
-//     K-steps wave w takes steps 2w and 2w+1 (128 contiguous bytes of each weight row), 16 steps per
-//     2048 columns, one 16-byte fragment per lane each, all issued up front;
-//   - both operands are read straight from global memory as 16-byte vectors along K (A = h rows,
-//     B = W rows), no transposes and no LDS on the way in: lane l holds row/column (l & 15) and the
-//     8 consecutive k's of chunk (l >> 4) of each step;
-//   - the rows of h pass in pairs of 16-row tiles (32 fragment loads in flight) against the weight
-//     fragments, which stay in registers when cols <= 2048 (SINGLE) and are re-read per pair (from
-//     cache) otherwise; rows beyond the batch re-read the last row and are never stored;
+//     K-steps wave w takes steps 2w and 2w+1 (128 contiguous bytes of each row), 16 steps per 2048
+//     columns;
+//   - weight fragments (B operand: lane l holds column l & 15, the 8 consecutive k's of chunk l >> 4
+//     of each step) are read straight from global memory, one 16-byte load per step, all issued up
+//     front; they stay in registers when cols <= 2048 (SINGLE) and are re-read per row pair (from
+//     cache) otherwise;
+//   - the rows of h pass in pairs of 16-row tiles.  Reading A fragments straight from global memory
+//     would touch 16 rows x 64 bytes per instruction, all 4 KB apart (one cache channel); instead each
+//     wave loads its own K-slices row by row (one row = 8 x 128 contiguous bytes per instruction),
+//     transposes them through its private slice of LDS into fragment order, and prefetches the next
+//     pair's rows while the matrix cores work on this one.  LDS slot (tile, lane of the load) holds
+//     16 rows x 16 bytes and is padded to 272 bytes so that 16 consecutive lanes hit all banks;
+//   - rows beyond the batch re-read the last row and are never stored;
 //   - per pair the 4 waves' partial tiles are summed through LDS in a fixed order; lane l of a tile
 //     holds column (l & 15), rows 4 * (l >> 4) .. + 3.
 // The pair loop is deliberately not unrolled: a kernel this short runs its code once, so code size
 // is instruction-fetch time.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int kMmSteps = 16;      // K-steps per wave per super-chunk (4 waves x 16 steps x 32 = 2048 columns)
+constexpr int kMmSteps = 16;        // K-steps per wave per super-chunk (4 waves x 16 steps x 32 = 2048 columns)
+constexpr int kMmSlotBytes = 272;   // 16 rows x 16 B + 16 B of padding
+constexpr int kMmWaveLds = 2 * 64 * kMmSlotBytes;   // one wave's staging area: 2 tiles x 64 slots
+
+// k offset of the 16-byte chunk that lane `l` of wave `wave` loads from a row (super-chunk at step s0);
+// the same chunk is fragment step l >> 2, k-chunk l & 3 of that wave.
+__device__ __forceinline__ int mm_k0(int s0, int wave, int l) {
+    return (s0 + (l >> 3) * 8 + wave * 2 + ((l >> 2) & 1)) * 32 + (l & 3) * 8;
+}
 
 template <bool FULL, bool AL, bool NT>
-__device__ __forceinline__ void mm_load_w(const bf16_t* wrow, int cols, int s0, int wave, int kq, unsigned (*wf)[4], int* koff, bool* ok) {
+__device__ __forceinline__ void mm_load_w(const bf16_t* wrow, int cols, int s0, int wave, int kq, unsigned (*wf)[4], bool* ok) {
 #pragma unroll
     for (int i = 0; i < kMmSteps; i++) {
         const int k0 = (s0 + (i >> 1) * 8 + wave * 2 + (i & 1)) * 32 + kq * 8;
         ok[i] = FULL || k0 < cols;                      // cols is a multiple of 8: a chunk is all in or all out
-        koff[i] = ok[i] ? k0 : 0;
-        load_vec<bf16_t, 16, AL, NT>(wrow + koff[i], wf[i]);
+        load_vec<bf16_t, 16, AL, NT>(wrow + (ok[i] ? k0 : 0), wf[i]);
     }
 }
 
+// the 32 rows of a pair, this wave's K-slices: one row per instruction
 template <bool FULL, bool AL>
-__device__ __forceinline__ void mm_pair(const bf16_t* h, int rows, int cols, int r0, int rc, const unsigned (*wf)[4], const int* koff,
-                                        const bool* ok, f32x4* acc) {
-    unsigned hf[2][kMmSteps][4];
-    const bf16_t* hrow[2];
+__device__ __forceinline__ void mm_load_h(const bf16_t* h, int rows, int cols, int r0, int s0, int wave, int lane, unsigned (*g)[4]) {
+    const int k0 = mm_k0(s0, wave, lane);
+    const int koff = (FULL || k0 < cols) ? k0 : 0;      // an out-of-range chunk meets a zero weight fragment
 #pragma unroll
-    for (int tt = 0; tt < 2; tt++) {
-        const int r = r0 + tt * 16 + rc;
-        hrow[tt] = h + (size_t)(r < rows ? r : rows - 1) * cols;
+    for (int r = 0; r < 32; r++) {
+        const int R = r0 + r < rows ? r0 + r : rows - 1;
+        load_vec<bf16_t, 16, AL, false>(h + (size_t)R * cols + koff, g[r]);
     }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void mm_stage_and_multiply(char* lds /* this wave's */, int lane, const unsigned (*g)[4],
+                                                      const unsigned (*wf)[4], const bool* ok, f32x4* acc) {
+    // LDS operations of one wave execute in order: these writes cannot overtake the previous pair's reads
 #pragma unroll
-    for (int i = 0; i < kMmSteps; i++)      // in the order the MFMAs consume them
+    for (int r = 0; r < 32; r++) {
+        v4u t;
+        t.x = g[r][0]; t.y = g[r][1]; t.z = g[r][2]; t.w = g[r][3];
+        *reinterpret_cast<v4u*>(lds + ((r >> 4) * 64 + lane) * kMmSlotBytes + (r & 15) * 16) = t;
+    }
+    // all 32 fragment reads first, then the MFMAs: left alone, the scheduler pairs each read with its
+    // use and the loop pays one LDS latency per fragment
+    v4u a[2][kMmSteps];
 #pragma unroll
-        for (int tt = 0; tt < 2; tt++) load_vec<bf16_t, 16, AL, false>(hrow[tt] + koff[i], hf[tt][i]);
-    // keep all 32 fragment loads ahead of the first MFMA: left alone, the scheduler sinks them next to
-    // their uses to save registers and the loop then pays one cache latency per fragment
+    for (int i = 0; i < kMmSteps; i++)
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++)
+            a[tt][i] = *reinterpret_cast<const v4u*>(lds + (tt * 64 + i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kMmSteps; i++) {
         v4u b;
         b.x = wf[i][0]; b.y = wf[i][1]; b.z = wf[i][2]; b.w = wf[i][3];
-        if (!FULL && !ok[i]) b = v4u{0u, 0u, 0u, 0u};      // a zero weight fragment cancels whatever A holds
+        if (!FULL && !ok[i]) b = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int tt = 0; tt < 2; tt++) {
-            v4u a;
-            a.x = hf[tt][i][0]; a.y = hf[tt][i][1]; a.z = hf[tt][i][2]; a.w = hf[tt][i][3];
-            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[tt], 0, 0, 0);
-        }
+        for (int tt = 0; tt < 2; tt++)
+            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[tt][i]), __builtin_bit_cast(bf16x8, b), acc[tt], 0, 0, 0);
     }
 }
 
 template <bool FULL, bool SINGLE, bool AL>
 __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols,
-                                               float* red /* LDS: [4 waves][2 tiles][64 lanes][4] */) {
+                                               char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][2 tiles][64 lanes][4] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rc = lane & 15, kq = lane >> 4;
     const int j0 = blockIdx.x * 16;
     const bf16_t* wrow = W + (size_t)((j0 + rc < n) ? j0 + rc : n - 1) * cols;
-    unsigned wf[kMmSteps][4];
-    int koff[kMmSteps];
+    char* lds = stage + wave * kMmWaveLds;
+    unsigned wf[kMmSteps][4], g[32][4];
     bool ok[kMmSteps];
-    if constexpr (SINGLE) mm_load_w<FULL, AL, true>(wrow, cols, 0, wave, kq, wf, koff, ok);   // streamed once: non-temporal
+    if constexpr (SINGLE) {
+        mm_load_w<FULL, AL, true>(wrow, cols, 0, wave, kq, wf, ok);   // streamed once: non-temporal
+        mm_load_h<FULL, AL>(h, rows, cols, 0, 0, wave, lane, g);
+    }
 #pragma unroll 1
     for (int r0 = 0; r0 < rows; r0 += 32) {
         f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
         if constexpr (SINGLE) {
-            mm_pair<FULL, AL>(h, rows, cols, r0, rc, wf, koff, ok, acc);
+            unsigned gnow[32][4];
+#pragma unroll
+            for (int r = 0; r < 32; r++)
+#pragma unroll
+                for (int e = 0; e < 4; e++) gnow[r][e] = g[r][e];
+            if (r0 + 32 < rows) mm_load_h<FULL, AL>(h, rows, cols, r0 + 32, 0, wave, lane, g);   // prefetch the next pair
+            mm_stage_and_multiply<FULL>(lds, lane, gnow, wf, ok, acc);
         } else {
 #pragma unroll 1
             for (int s0 = 0; s0 * 32 < cols; s0 += 4 * kMmSteps) {
-                mm_load_w<FULL, AL, false>(wrow, cols, s0, wave, kq, wf, koff, ok);
-                mm_pair<FULL, AL>(h, rows, cols, r0, rc, wf, koff, ok, acc);
+                mm_load_w<FULL, AL, false>(wrow, cols, s0, wave, kq, wf, ok);
+                mm_load_h<FULL, AL>(h, rows, cols, r0, s0, wave, lane, g);
+                mm_stage_and_multiply<FULL>(lds, lane, g, wf, ok, acc);
             }
         }
         // sum the 4 waves' partial tiles in a fixed order and store
@@ -699,10 +732,11 @@ __global__ __launch_bounds__(kBlock) void k_gemm_mfma_bf16(GemvArgs p) {
     const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
     const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
     bf16_t* y = static_cast<bf16_t*>(p.out);
+    __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[4 * 2 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);   // rows keep the alignment: cols is a multiple of 8
-    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, red);
-    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, red);
+    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, stage, red);
+    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, stage, red);
 }
 
 // ---- batched multi-tensor copy -----------------------------------------------------------------
@@ -789,12 +823,12 @@ template <typename T, int OP>
 bool plan_ew_t(int ind, long long n, Launch* out) {
     constexpr int NV16 = 16 / (int)sizeof(T), NV4 = 4 / (int)sizeof(T);
     const long long bytes = n * (long long)sizeof(T);
-    const bool narrow = OP == kGelu && n <= (sizeof(T) == 4 ? (1ll << 20) : (1ll << 15));
+    const bool narrow = OP == kGelu && n <= (1ll << 20);
     out->block = dim3(kBlock);
     if (narrow) {
         out->fn = ew_by_ind<T, OP, 4, 1, unsigned>(ind);
         out->grid = dim3(blocks_for(n, (long long)kBlock * NV4));
-    } else if (bytes <= (256ll << 10)) {
+    } else if (bytes <= (4ll << 20)) {
         out->fn = ew_by_ind<T, OP, 16, 1, unsigned>(ind);
         out->grid = dim3(blocks_for(n, (long long)kBlock * NV16));
     } else if (n < (1ll << 31)) {
@@ -894,7 +928,7 @@ template <typename T>
 bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     constexpr int NV = 16 / (int)sizeof(T);
     if constexpr (sizeof(T) == 2) {
-        if (rows > 1 && cols % 8 == 0) {   // a dense contraction: matrix cores
+        if (rows > 8 && cols % 8 == 0) {   // a dense contraction: matrix cores (up to 8 rows the vector form below is faster)
             out->block = dim3(kBlock);
             out->grid = dim3(blocks_for(n, 16));
             constexpr int kSuper = 32 * 4 * kMmSteps;   // columns one pass of the 4 waves covers
