@@ -90,6 +90,13 @@ def main() -> int:
     us_ind_memcpy = timed(pg.GRAPH_INDIRECT)
     chain.set_table_refresh(pg.TABLE_KERNARG)
     log(f"[bench] graph_indirect with a pinned-memcpy table refresh: {us_ind_memcpy:.1f} us/iteration")
+    # the baselines the two refresh designs stand against: the host rewrites the external-reading
+    # kernel nodes' arguments before each launch; the copy refresh as one memcpy per tensor
+    us_update = timed(pg.GRAPH_UPDATE)
+    chain.set_copy_refresh(pg.COPY_MEMCPY)
+    us_copy_memcpy = timed(pg.GRAPH_COPY)
+    chain.set_copy_refresh(pg.COPY_KERNEL)
+    log(f"[bench] graph with host-side node updates: {us_update:.1f}; graph_copy with per-tensor memcpy: {us_copy_memcpy:.1f} us/iteration")
 
     # ------------------------------------------------------------------ the dominant kernel alone: GEMV 2048x2048, HIP events on the launch stream
     # A graph of the chain's 120 GEMV launches and nothing else (same kernel, same launch shape, the
@@ -153,6 +160,12 @@ def main() -> int:
         for name, mode in (("eager", pg.EAGER), ("graph_copy", pg.GRAPH_COPY), ("graph_indirect", pg.GRAPH_INDIRECT)):
             chain3.time_loop(mode, sets3, 3, stream)
             us3[name] = chain3.time_loop(mode, sets3, 20, stream)
+        chain3.time_loop(pg.GRAPH_UPDATE, sets3, 3, stream)
+        us3["graph_update"] = chain3.time_loop(pg.GRAPH_UPDATE, sets3, 20, stream)
+        chain3.set_copy_refresh(pg.COPY_MEMCPY)
+        chain3.time_loop(pg.GRAPH_COPY, sets3, 3, stream)
+        us3["graph_copy_per_tensor_memcpy"] = chain3.time_loop(pg.GRAPH_COPY, sets3, 20, stream)
+        chain3.set_copy_refresh(pg.COPY_KERNEL)
         # a plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick the
         # hardware-counter byte counts of a profiled run are scaled by
         cal_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -203,6 +216,7 @@ def main() -> int:
         "launches_per_s": {m: n_k / us[m] * 1e6 for m in us},
         "speedup_vs_eager": {m: us["eager"] / us[m] for m in us},
         "graph_indirect_memcpy_table_us": us_ind_memcpy,
+        "graph_host_node_update_us": us_update, "graph_copy_per_tensor_memcpy_us": us_copy_memcpy,
         "selection": {"cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()], "mode": sel.tolist()},
         "idle_gap_fraction": None,   # needs per-kernel durations: taken from the rocprofv3 kernel trace, reported with the profile summaries
         "chain_level_GBps": chain_level, "chain_level_hbm_frac": {m: chain_level[m] / HBM_PEAK for m in us},

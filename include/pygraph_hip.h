@@ -104,6 +104,13 @@ typedef enum {
     PG_TABLE_MEMCPY = 1    /* hipMemcpyAsync from a ring of pinned staging slots               */
 } pg_table_refresh;
 
+/* How a copy-mode replay moves the data of the external inputs into the placeholders (Sec. 2.2:
+ * the deployed systems copy parameter by parameter; Sec. 5, table of bytes copied). */
+typedef enum {
+    PG_COPY_KERNEL = 0,    /* one batched copy kernel per <= 448 tensors (this library's design)  */
+    PG_COPY_MEMCPY = 1     /* one device-to-device hipMemcpyAsync per tensor (the paper's baseline) */
+} pg_copy_refresh;
+
 /* Bytes of workspace [dev] a chain needs.  Host only.  The descriptor is validated as in
  * pg_chain_build as far as that is possible without the weight descriptors.  ext / ints: [host]
  * arrays of n_ext / n_int tensor descriptors. */
@@ -152,6 +159,17 @@ pg_status pg_replay_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void 
  * graph launch per segment; kernels dereference their table slots first (Sec. 3, Sec. 4). */
 pg_status pg_replay_indirect(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
 
+/* One iteration with neither copies nor indirection: a third graph per segment, built from explicit
+ * kernel nodes with direct pointers, whose external-reading nodes get their argument blocks
+ * rewritten from the host before every launch (hipGraphExecKernelNodeSetParams).  This is the
+ * alternative the graph API itself offers to what Sec. 3 "Parameter Indirection" does on the
+ * device: one host call per external-reading kernel and replay, instead of 8 bytes per external.
+ * The first call builds and instantiates the graphs (it synchronises the stream and must not be
+ * captured).  Two executable instances alternate, and before an instance is rewritten the call
+ * waits on the host for that instance's previous launch to finish, so a rewrite never touches
+ * arguments a running launch may still read.  Results are identical to the other modes'. */
+pg_status pg_replay_update(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
+
 /* Selection rule (Sec. 4.3): mode_out[s] = the available variant of least cost, each segment on
  * its own.  cost_us [host] is [n_seg][3] in pg_mode order; a non-finite entry marks a variant that
  * does not exist; ties keep the earlier mode.  A negative cost or a segment with no variant is
@@ -176,8 +194,8 @@ pg_status pg_run_selected(pg_chain *chain, const uint8_t *mode, const void *cons
 pg_status pg_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
 pg_status pg_refresh_indirect(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
 
-/* Timed loop for benchmarks: `iters` iterations of one mode (pg_mode, or 3 = pg_run_selected with
- * `mode_per_segment`), iteration t using pointer set t % n_sets of ext_sets [host]
+/* Timed loop for benchmarks: `iters` iterations of one mode (pg_mode, 3 = pg_run_selected with
+ * `mode_per_segment`, 4 = pg_replay_update), iteration t using pointer set t % n_sets of ext_sets [host]
  * ([n_sets][n_ext] device pointers), one stream synchronisation at the end; returns mean
  * microseconds per iteration measured on the host clock. */
 pg_status pg_time_loop(pg_chain *chain, int32_t mode, const uint8_t *mode_per_segment,
@@ -201,6 +219,7 @@ pg_status pg_chain_placeholder(const pg_chain *chain, int32_t ext_index, void **
 pg_status pg_chain_pointer_table(const pg_chain *chain, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);
 pg_status pg_set_table_refresh(pg_chain *chain, int32_t how /* pg_table_refresh */);
+pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */);
 void pg_chain_destroy(pg_chain *chain);
 
 const char *pg_last_error(void);

@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     GRAPH_COPY,
     GRAPH_INDIRECT,
     SELECTED,
+    GRAPH_UPDATE,
     TABLE_KERNARG,
     TABLE_MEMCPY,
+    COPY_KERNEL,
+    COPY_MEMCPY,
 )

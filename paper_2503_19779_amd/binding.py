@@ -14,8 +14,9 @@ import numpy as np
 
 from . import build as _build
 
-EAGER, GRAPH_COPY, GRAPH_INDIRECT, SELECTED = 0, 1, 2, 3
+EAGER, GRAPH_COPY, GRAPH_INDIRECT, SELECTED, GRAPH_UPDATE = 0, 1, 2, 3, 4
 TABLE_KERNARG, TABLE_MEMCPY = 0, 1
+COPY_KERNEL, COPY_MEMCPY = 0, 1
 
 _DT = {"f32": 0, "bf16": 1}
 _OP = {"add": 0, "mul": 1, "gelu": 2, "rmsnorm": 3, "gemv": 4, "scale_bias_relu": 5}
@@ -67,7 +68,7 @@ def lib():
         L.pg_chain_workspace_bytes.argtypes = [KP, i32, TP, i32, TP, i32, C.POINTER(C.c_size_t)]
         L.pg_chain_build.argtypes = [KP, i32, TP, i32, TP, i32, PP, TP, i32, vp, C.c_size_t, C.POINTER(vp)]
         L.pg_capture.argtypes = [vp, vp]
-        for name in ("pg_eager", "pg_replay_copy", "pg_replay_indirect", "pg_refresh_copy", "pg_refresh_indirect"):
+        for name in ("pg_eager", "pg_replay_copy", "pg_replay_indirect", "pg_replay_update", "pg_refresh_copy", "pg_refresh_indirect"):
             getattr(L, name).argtypes = [vp, PP, vp]
         L.pg_eager_range.argtypes = [vp, PP, i32, i32, vp]
         L.pg_select.argtypes = [C.POINTER(C.c_double), i32, C.POINTER(C.c_uint8)]
@@ -81,6 +82,7 @@ def lib():
         L.pg_chain_pointer_table.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.pg_chain_stats.argtypes = [vp, C.POINTER(_Stats)]
         L.pg_set_table_refresh.argtypes = [vp, i32]
+        L.pg_set_copy_refresh.argtypes = [vp, i32]
         L.pg_chain_destroy.argtypes = [vp]
         L.pg_chain_destroy.restype = None
         L.pg_last_error.restype = C.c_char_p
@@ -235,6 +237,9 @@ class Chain:
     def replay_indirect(self, ext, stream):
         _check(lib().pg_replay_indirect(self._h, self._ext(ext), self._s(stream)))
 
+    def replay_update(self, ext, stream):
+        _check(lib().pg_replay_update(self._h, self._ext(ext), self._s(stream)))
+
     def refresh_copy(self, ext, stream):
         _check(lib().pg_refresh_copy(self._h, self._ext(ext), self._s(stream)))
 
@@ -286,6 +291,9 @@ class Chain:
 
     def set_table_refresh(self, how: int):
         _check(lib().pg_set_table_refresh(self._h, how))
+
+    def set_copy_refresh(self, how: int):
+        _check(lib().pg_set_copy_refresh(self._h, how))
 
     # -- views into the workspace
     def _view(self, fn, index, dtype: Optional[str]):

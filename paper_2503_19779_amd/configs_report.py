@@ -1,6 +1,8 @@
 """Timing report for the benchmark chains other than the one bench.py times:
 
-    python -m paper_2503_19779_amd.configs_report --config 1 3 4 5
+    python -m paper_2503_19779_amd.configs_report --config 0 1 3 4 5
+
+(config 0 is the launch floor: 512 dependent kernels on 64 elements each.)
 
 Per chain: capture, slow-path profile -> cost table -> selection, then microseconds per iteration
 for eager, graph-copy, graph-indirect and the selected mixture (back-to-back iterations on one
@@ -56,6 +58,14 @@ def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile
                               ("graph_indirect", pg.GRAPH_INDIRECT, None), ("selected", pg.SELECTED, sel)):
         chain.time_loop(mode, sets, warmup, stream, modes)
         us[name] = chain.time_loop(mode, sets, iters, stream, modes)
+    # the two baselines the refresh designs are measured against: host-side rewrite of the kernel
+    # nodes' arguments, and the copy refresh as one device-to-device memcpy per tensor
+    chain.time_loop(pg.GRAPH_UPDATE, sets, warmup, stream)
+    us["graph_update"] = chain.time_loop(pg.GRAPH_UPDATE, sets, iters, stream)
+    chain.set_copy_refresh(pg.COPY_MEMCPY)
+    chain.time_loop(pg.GRAPH_COPY, sets, warmup, stream)
+    us["graph_copy_per_tensor_memcpy"] = chain.time_loop(pg.GRAPH_COPY, sets, iters, stream)
+    chain.set_copy_refresh(pg.COPY_KERNEL)
     st = chain.stats()
     return chain, {"us_per_iteration": us, "capture_ms": cap_ms,
                    "cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()],
@@ -88,7 +98,13 @@ def main() -> int:
         return make
 
     for cfg in args.config:
-        if cfg == 1:
+        if cfg == 0:
+            # launch floor: 512 dependent kernels on 64 elements each, so the time per kernel is the
+            # cost of dispatching one dependent kernel (host launch for eager, graph node for replay)
+            spec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
+            chain, r = time_chain(pg, torch, spec, [], host_sets(spec, 3), args.iters, 10, stream)
+            r["us_per_kernel"] = {m: v / len(spec.kernels) for m, v in r["us_per_iteration"].items()}
+        elif cfg == 1:
             spec = elementwise_chain()
             chain, r = time_chain(pg, torch, spec, [], host_sets(spec, 3), args.iters, 10, stream)
         elif cfg == 3:

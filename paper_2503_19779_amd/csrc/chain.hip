@@ -58,7 +58,7 @@ union ArgBlock {
 
 struct KernelRec {
     pgk::Launch direct, indirect;   // same shape, different kernel variant
-    ArgBlock a_eager, a_copy, a_ind;
+    ArgBlock a_eager, a_copy, a_ind, a_upd;
     int n_in = 0;
     int ind_mask = 0;               // operands that are external
     int ext_of[3] = {-1, -1, -1};
@@ -80,6 +80,10 @@ struct Segment {
     int copy_list = -1;             // index into copy_lists
     hipGraph_t g_copy = nullptr, g_ind = nullptr;
     hipGraphExec_t x_copy = nullptr, x_ind = nullptr;
+    // host-updated variant: explicit kernel nodes in chain order, two executable instances
+    hipGraph_t g_upd = nullptr;
+    hipGraphExec_t x_upd[2] = {nullptr, nullptr};
+    std::vector<hipGraphNode_t> nodes;
 };
 
 }  // namespace
@@ -98,6 +102,12 @@ struct pg_chain {
     std::vector<std::pair<int, int>> eager_fix;   // (kernel, operand) pairs that take a caller pointer
     bool captured = false;
     int table_how = PG_TABLE_KERNARG;
+    int copy_how = PG_COPY_KERNEL;
+    // host-updated graphs: which instance the next replay rewrites, and when each was last launched
+    bool upd_built = false;
+    unsigned long long upd_cnt = 0;
+    hipEvent_t upd_ev[2] = {nullptr, nullptr};
+    bool upd_used[2] = {false, false};
     // pinned staging ring for PG_TABLE_MEMCPY
     static constexpr int kRing = 64;
     void* staging = nullptr;
@@ -367,6 +377,14 @@ pg_status run_eager_range(pg_chain* c, int k0, int k1, const void* const* ext, h
 
 pg_status run_copy_list(pg_chain* c, int list, const void* const* ext, hipStream_t s) {
     CopyList& L = c->copy_lists[list];
+    if (c->copy_how == PG_COPY_MEMCPY) {
+        for (size_t t = 0; t < L.ext.size(); t++) {
+            const int e = L.ext[t];
+            PG_HIP(hipMemcpyAsync(c->ws + c->ph_off[e], ext[e], (size_t)c->ext[e].numel * elem_bytes(c->ext[e].dtype),
+                                  hipMemcpyDeviceToDevice, s));
+        }
+        return PG_OK;
+    }
     for (const auto& g : L.groups) {
         if (g.c1 == g.c0) continue;
         pgk::CopyArgs a;
@@ -411,6 +429,10 @@ pg_status write_table(pg_chain* c, const void* const* ext, hipStream_t s) {
 
 void destroy_graphs(pg_chain* c) {
     for (auto& s : c->seg) {
+        for (auto& x : s.x_upd) { if (x) (void)hipGraphExecDestroy(x); x = nullptr; }
+        if (s.g_upd) (void)hipGraphDestroy(s.g_upd);
+        s.g_upd = nullptr;
+        s.nodes.clear();
         if (s.x_ind && s.x_ind != s.x_copy) (void)hipGraphExecDestroy(s.x_ind);
         if (s.g_ind && s.g_ind != s.g_copy) (void)hipGraphDestroy(s.g_ind);
         if (s.x_copy) (void)hipGraphExecDestroy(s.x_copy);
@@ -419,6 +441,76 @@ void destroy_graphs(pg_chain* c) {
         s.g_copy = s.g_ind = nullptr;
     }
     c->captured = false;
+    c->upd_built = false;
+    c->upd_used[0] = c->upd_used[1] = false;
+}
+
+hipKernelNodeParams node_params(KernelRec& r, void** slot) {
+    hipKernelNodeParams p{};
+    p.func = const_cast<void*>(r.direct.fn);
+    p.gridDim = r.direct.grid;
+    p.blockDim = r.direct.block;
+    p.sharedMemBytes = 0;
+    slot[0] = &r.a_upd;          // every kernel takes its argument block as one by-value struct
+    p.kernelParams = slot;
+    p.extra = nullptr;
+    return p;
+}
+
+pg_status build_update_graphs(pg_chain* c, hipStream_t s) {
+    if (!c->upd_ev[0]) {
+        PG_HIP(hipEventCreateWithFlags(&c->upd_ev[0], hipEventDisableTiming));
+        PG_HIP(hipEventCreateWithFlags(&c->upd_ev[1], hipEventDisableTiming));
+    }
+    for (auto& sg : c->seg) {
+        PG_HIP(hipGraphCreate(&sg.g_upd, 0));
+        sg.nodes.clear();
+        hipGraphNode_t prev = nullptr;
+        for (int i = sg.k0; i < sg.k1; i++) {
+            KernelRec& r = c->rec[i];
+            r.a_upd = r.a_copy;   // external operands start at the placeholders: valid addresses of the right size
+            void* slot[1];
+            hipKernelNodeParams p = node_params(r, slot);
+            hipGraphNode_t n = nullptr;
+            PG_HIP(hipGraphAddKernelNode(&n, sg.g_upd, prev ? &prev : nullptr, prev ? 1 : 0, &p));
+            sg.nodes.push_back(n);
+            prev = n;
+        }
+        for (auto& x : sg.x_upd) {
+            PG_HIP(hipGraphInstantiate(&x, sg.g_upd, nullptr, nullptr, 0));
+            PG_HIP(hipGraphUpload(x, s));
+        }
+    }
+    PG_HIP(hipStreamSynchronize(s));
+    c->upd_built = true;
+    return PG_OK;
+}
+
+pg_status run_update(pg_chain* c, const void* const* ext, hipStream_t s) {
+    if (!c->upd_built) {
+        pg_status st = build_update_graphs(c, s);
+        if (st) { for (auto& sg : c->seg) { for (auto& x : sg.x_upd) { if (x) (void)hipGraphExecDestroy(x); x = nullptr; }
+                                            if (sg.g_upd) (void)hipGraphDestroy(sg.g_upd); sg.g_upd = nullptr; sg.nodes.clear(); }
+                  return st; }
+    }
+    const int which = (int)(c->upd_cnt & 1);
+    if (c->upd_used[which]) PG_HIP(hipEventSynchronize(c->upd_ev[which]));
+    for (auto& sg : c->seg) {
+        for (int i = sg.k0; i < sg.k1; i++) {
+            KernelRec& r = c->rec[i];
+            if (!r.ind_mask) continue;
+            for (int j = 0; j < r.n_in; j++)
+                if (r.ext_of[j] >= 0) r.a_upd.ptr[1 + j] = ext[r.ext_of[j]];
+            void* slot[1];
+            hipKernelNodeParams p = node_params(r, slot);
+            PG_HIP(hipGraphExecKernelNodeSetParams(sg.x_upd[which], sg.nodes[i - sg.k0], &p));
+        }
+        PG_HIP(hipGraphLaunch(sg.x_upd[which], s));
+    }
+    PG_HIP(hipEventRecord(c->upd_ev[which], s));
+    c->upd_used[which] = true;
+    c->upd_cnt++;
+    return PG_OK;
 }
 
 pg_status capture_segment(pg_chain* c, Segment& sg, bool indirect, hipStream_t s, hipGraph_t* g_out, hipGraphExec_t* x_out) {
@@ -622,6 +714,18 @@ pg_status pg_replay_indirect(pg_chain* c, const void* const* ext, void* hip_stre
     return PG_OK;
 }
 
+pg_status pg_replay_update(pg_chain* c, const void* const* ext, void* hip_stream) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (!c->upd_built) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        PG_HIP(hipStreamIsCapturing(s, &cs));
+        if (cs != hipStreamCaptureStatusNone) return fail(PG_EINVAL, "the first pg_replay_update builds graphs and cannot run on a capturing stream");
+    }
+    return run_update(c, ext, s);
+}
+
 pg_status pg_run_selected(pg_chain* c, const uint8_t* mode, const void* const* ext, void* hip_stream) {
     pg_status st = check_call(c, ext, hip_stream, true);
     if (st) return st;
@@ -684,7 +788,7 @@ pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segmen
     for (int i = 0; i < n_sets; i++)
         if ((st = check_call(c, ext_sets + (size_t)i * n_ext, hip_stream, mode != PG_EAGER))) return st;
     if (mode == 3 && !mode_per_segment) return fail(PG_EINVAL, "null mode array");
-    if (mode < 0 || mode > 3) return fail(PG_EINVAL, "bad mode");
+    if (mode < 0 || mode > 4) return fail(PG_EINVAL, "bad mode");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     PG_HIP(hipStreamSynchronize(s));
     const double t0 = now_us();
@@ -694,6 +798,7 @@ pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segmen
         case PG_EAGER: st = run_eager_range(c, 0, (int)c->k.size(), ext, s); break;
         case PG_GRAPH_COPY: st = pg_replay_copy(c, ext, hip_stream); break;
         case PG_GRAPH_INDIRECT: st = pg_replay_indirect(c, ext, hip_stream); break;
+        case 4: st = pg_replay_update(c, ext, hip_stream); break;
         default: st = pg_run_selected(c, mode_per_segment, ext, hip_stream); break;
         }
         if (st) return st;
@@ -812,9 +917,17 @@ pg_status pg_set_table_refresh(pg_chain* c, int32_t how) {
     return PG_OK;
 }
 
+pg_status pg_set_copy_refresh(pg_chain* c, int32_t how) {
+    if (!c || (how != PG_COPY_KERNEL && how != PG_COPY_MEMCPY)) return fail(PG_EINVAL, "bad copy refresh kind");
+    c->copy_how = how;
+    return PG_OK;
+}
+
 void pg_chain_destroy(pg_chain* c) {
     if (!c) return;
     destroy_graphs(c);
+    if (c->upd_ev[0]) (void)hipEventDestroy(c->upd_ev[0]);
+    if (c->upd_ev[1]) (void)hipEventDestroy(c->upd_ev[1]);
     if (c->ring_ev[0]) (void)hipEventDestroy(c->ring_ev[0]);
     if (c->ring_ev[1]) (void)hipEventDestroy(c->ring_ev[1]);
     if (c->staging) (void)hipHostFree(c->staging);

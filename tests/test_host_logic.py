@@ -212,7 +212,7 @@ def test_calls_out_of_order_or_with_bad_pointers():
     with pytest.raises(pg.PgError) as e:
         ch.replay_copy(ext, fake_stream)
     assert e.value.status == 2                                                        # PG_ESTATE: not captured
-    for call in (ch.replay_indirect, ch.refresh_copy, ch.refresh_indirect):
+    for call in (ch.replay_indirect, ch.replay_update, ch.refresh_copy, ch.refresh_indirect):
         with pytest.raises(pg.PgError) as e:
             call(ext, fake_stream)
         assert e.value.status == 2
@@ -232,4 +232,8 @@ def test_calls_out_of_order_or_with_bad_pointers():
         ch.capture(0)
     with pytest.raises(pg.PgError):
         ch.set_table_refresh(7)
+    with pytest.raises(pg.PgError):
+        ch.set_copy_refresh(-1)
+    ch.set_copy_refresh(pg.COPY_MEMCPY)
+    ch.set_copy_refresh(pg.COPY_KERNEL)
     ch.close()
