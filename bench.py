@@ -35,6 +35,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-copy-bench", action="store_true", help="skip the copy-kernel bandwidth leg (config 3 sizes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-refresh-baselines", action="store_true",
+                    help="skip the two refresh baselines (host-side node updates, per-tensor memcpy); the profiler runs use this")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
     args = ap.parse_args()
@@ -92,11 +94,14 @@ def main() -> int:
     log(f"[bench] graph_indirect with a pinned-memcpy table refresh: {us_ind_memcpy:.1f} us/iteration")
     # the baselines the two refresh designs stand against: the host rewrites the external-reading
     # kernel nodes' arguments before each launch; the copy refresh as one memcpy per tensor
-    us_update = timed(pg.GRAPH_UPDATE)
-    chain.set_copy_refresh(pg.COPY_MEMCPY)
-    us_copy_memcpy = timed(pg.GRAPH_COPY)
-    chain.set_copy_refresh(pg.COPY_KERNEL)
-    log(f"[bench] graph with host-side node updates: {us_update:.1f}; graph_copy with per-tensor memcpy: {us_copy_memcpy:.1f} us/iteration")
+    us_update = us_copy_memcpy = None
+    if not args.no_refresh_baselines:
+        us_update = timed(pg.GRAPH_UPDATE)
+        log(f"[bench] graph with host-side node updates: {us_update:.1f} us/iteration")
+        chain.set_copy_refresh(pg.COPY_MEMCPY)
+        us_copy_memcpy = timed(pg.GRAPH_COPY)
+        chain.set_copy_refresh(pg.COPY_KERNEL)
+        log(f"[bench] graph_copy with per-tensor memcpy: {us_copy_memcpy:.1f} us/iteration")
 
     # ------------------------------------------------------------------ the dominant kernel alone: GEMV 2048x2048, HIP events on the launch stream
     # A graph of the chain's 120 GEMV launches and nothing else (same kernel, same launch shape, the
@@ -130,7 +135,7 @@ def main() -> int:
                 "how": "HIP events on the launch stream around 50 replays of a graph of the chain's 120 GEMV launches; per-launch time includes the inter-kernel dispatch gap",
                 # HBM bytes per launch from the hardware-counter runs (FETCH_SIZE x 1.9996 + WRITE_SIZE x 1.0000,
                 # factors from a plain 256 MiB copy in the same run); the summary sits beside the other profiles
-                "traffic": 8.462e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
+                "traffic": 8.471e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
 
@@ -160,12 +165,14 @@ def main() -> int:
         for name, mode in (("eager", pg.EAGER), ("graph_copy", pg.GRAPH_COPY), ("graph_indirect", pg.GRAPH_INDIRECT)):
             chain3.time_loop(mode, sets3, 3, stream)
             us3[name] = chain3.time_loop(mode, sets3, 20, stream)
-        chain3.time_loop(pg.GRAPH_UPDATE, sets3, 3, stream)
-        us3["graph_update"] = chain3.time_loop(pg.GRAPH_UPDATE, sets3, 20, stream)
-        chain3.set_copy_refresh(pg.COPY_MEMCPY)
-        chain3.time_loop(pg.GRAPH_COPY, sets3, 3, stream)
-        us3["graph_copy_per_tensor_memcpy"] = chain3.time_loop(pg.GRAPH_COPY, sets3, 20, stream)
-        chain3.set_copy_refresh(pg.COPY_KERNEL)
+        if not args.no_refresh_baselines:
+            chain3.time_loop(pg.GRAPH_UPDATE, sets3, 3, stream)
+            us3["graph_update"] = chain3.time_loop(pg.GRAPH_UPDATE, sets3, 20, stream)
+            log(f"[bench] refresh-stress chain, host-side node updates: {us3['graph_update']:.1f} us/iteration")
+            chain3.set_copy_refresh(pg.COPY_MEMCPY)
+            chain3.time_loop(pg.GRAPH_COPY, sets3, 3, stream)
+            us3["graph_copy_per_tensor_memcpy"] = chain3.time_loop(pg.GRAPH_COPY, sets3, 20, stream)
+            chain3.set_copy_refresh(pg.COPY_KERNEL)
         # a plain device-to-device copy of known size (256 MiB read + 256 MiB written): the yardstick the
         # hardware-counter byte counts of a profiled run are scaled by
         cal_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
