@@ -2,7 +2,8 @@
 
     python -m paper_2503_19779_amd.configs_report --config 0 1 3 4 5
 
-(config 0 is the launch floor: 512 dependent kernels on 64 elements each.)
+(config 0 is the launch floor: 512 dependent kernels on 64 elements each; config 6 sweeps the
+batch-1 GEMV over matrix sizes.)
 
 Per chain: capture, slow-path profile -> cost table -> selection, then microseconds per iteration
 for eager, graph-copy, graph-indirect and the selected mixture (back-to-back iterations on one
@@ -98,6 +99,29 @@ def main() -> int:
         return make
 
     for cfg in args.config:
+        if cfg == 6:
+            # The batch-1 GEMV kernel away from the launch-bound size: graphs of 24 launches over
+            # matrices that together exceed the 256 MB memory-side cache, per-launch time and bandwidth.
+            # Shows what part of the 2048 x 2048 figure is the fixed cost of a dispatch slot.
+            from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, WEIGHT
+            rows_out = []
+            for H in (1024, 2048, 4096, 8192, 16384):
+                n_mat = max(2, min(24, (640 << 20) // (H * H * 2) + 1))
+                mats = [torch.randn(H * H, device="cuda", dtype=torch.float32).mul_(0.02).to(torch.bfloat16) for _ in range(n_mat)]
+                vec = torch.randn(H, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                ks = [KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s % n_mat), Ref(WEIGHT, n_mat)), H, rows=1, cols=H) for s in range(24)]
+                spec = ChainSpec(f"gemv_{H}", ks, [], [TensorSpec("bf16", H)], [TensorSpec("bf16", H * H)] * n_mat + [TensorSpec("bf16", H)], [0])
+                chain = pg.Chain(spec, mats + [vec])
+                chain.capture(stream)
+                chain.time_loop(pg.GRAPH_COPY, [[]], 5, stream)
+                us = chain.time_loop(pg.GRAPH_COPY, [[]], 20, stream) / 24
+                chain.close()
+                b = H * H * 2 + 4 * H
+                rows_out.append({"n": H, "cols": H, "matrices": n_mat, "us_per_launch": us, "GBps": b / us / 1e3, "hbm_frac": b / us / 1e3 / HBM_PEAK})
+                log(f"[configs] GEMV {H} x {H}: {us:.2f} us per launch, {b / us / 1e3:.0f} GB/s")
+                del mats, vec
+            print(json.dumps({"config": 6, "workload": "batch-1 bf16 GEMV size sweep, 24 launches per graph", "gemv": rows_out}), flush=True)
+            continue
         if cfg == 0:
             # launch floor: 512 dependent kernels on 64 elements each, so the time per kernel is the
             # cost of dispatching one dependent kernel (host launch for eager, graph node for replay)
