@@ -335,6 +335,8 @@ pg_status make_records(pg_chain* c) {
             return fail(PG_EINVAL, "kernel %d: no device kernel for op %d dtype %d", i, d.op, d.dtype);
         if (r.direct.grid.x != r.indirect.grid.x || r.direct.block.x != r.indirect.block.x)
             return fail(PG_EINVAL, "kernel %d: direct and indirect forms disagree on the launch shape", i);
+        if (d.op == PG_GEMV)
+            for (ArgBlock* a : {&r.a_eager, &r.a_copy, &r.a_ind}) a->gemv.row_groups = (int)r.direct.gemm_row_groups;
     }
     return PG_OK;
 }
@@ -427,12 +429,20 @@ pg_status write_table(pg_chain* c, const void* const* ext, hipStream_t s) {
     return PG_OK;
 }
 
-void destroy_graphs(pg_chain* c) {
+void destroy_update_graphs(pg_chain* c) {
     for (auto& s : c->seg) {
         for (auto& x : s.x_upd) { if (x) (void)hipGraphExecDestroy(x); x = nullptr; }
         if (s.g_upd) (void)hipGraphDestroy(s.g_upd);
         s.g_upd = nullptr;
         s.nodes.clear();
+    }
+    c->upd_built = false;
+    c->upd_used[0] = c->upd_used[1] = false;
+}
+
+void destroy_graphs(pg_chain* c) {
+    destroy_update_graphs(c);
+    for (auto& s : c->seg) {
         if (s.x_ind && s.x_ind != s.x_copy) (void)hipGraphExecDestroy(s.x_ind);
         if (s.g_ind && s.g_ind != s.g_copy) (void)hipGraphDestroy(s.g_ind);
         if (s.x_copy) (void)hipGraphExecDestroy(s.x_copy);
@@ -441,8 +451,6 @@ void destroy_graphs(pg_chain* c) {
         s.g_copy = s.g_ind = nullptr;
     }
     c->captured = false;
-    c->upd_built = false;
-    c->upd_used[0] = c->upd_used[1] = false;
 }
 
 hipKernelNodeParams node_params(KernelRec& r, void** slot) {
@@ -489,9 +497,7 @@ pg_status build_update_graphs(pg_chain* c, hipStream_t s) {
 pg_status run_update(pg_chain* c, const void* const* ext, hipStream_t s) {
     if (!c->upd_built) {
         pg_status st = build_update_graphs(c, s);
-        if (st) { for (auto& sg : c->seg) { for (auto& x : sg.x_upd) { if (x) (void)hipGraphExecDestroy(x); x = nullptr; }
-                                            if (sg.g_upd) (void)hipGraphDestroy(sg.g_upd); sg.g_upd = nullptr; sg.nodes.clear(); }
-                  return st; }
+        if (st) { destroy_update_graphs(c); return st; }
     }
     const int which = (int)(c->upd_cnt & 1);
     if (c->upd_used[which]) PG_HIP(hipEventSynchronize(c->upd_ev[which]));

@@ -36,6 +36,7 @@ struct GemvArgs {
     int rows;
     int n;
     int cols;
+    int row_groups;      // matrix-core form only: the grid is (column blocks) x (row groups); from Launch
 };
 struct SbrArgs {
     void* out;
@@ -76,6 +77,7 @@ struct Launch {
     unsigned arg_bytes = 0;          // size of the kernel's argument block
     dim3 grid{1, 1, 1};
     dim3 block{1, 1, 1};
+    unsigned gemm_row_groups = 0;    // GEMV on the matrix cores: goes into GemvArgs::row_groups (0 = other kernels)
 };
 
 struct Shape {

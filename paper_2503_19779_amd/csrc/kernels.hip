@@ -590,29 +590,32 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
 // Batched bf16 with whole 16-byte vectors per row: y[rows, n] = h[rows, cols] * W[n, cols]^T is a
 // dense contraction once rows > 1, so it goes to the matrix cores (v_mfma_f32_16x16x32_bf16, fp32
 // accumulate).  Still weight-streaming bound up to rows ~ 128: every weight is read once from HBM.
-//   - one workgroup per 16 output columns; its 4 waves split K: of every 8 consecutive 32-wide
-//     K-steps wave w takes steps 2w and 2w+1 (128 contiguous bytes of each row), 16 steps per 2048
-//     columns;
+//   - a workgroup owns 16 output columns and one group of 16-row tiles of h; the grid is
+//     (column blocks) x (row groups), column block fastest, so that the row groups of one column
+//     block land on the same XCD (workgroups go to the 8 XCDs round-robin) and all but the first find
+//     the weights in its L2;
+//   - its 4 waves split K: of every 8 consecutive 32-wide K-steps wave w takes steps 2w and 2w+1 (128
+//     contiguous bytes of each row), 16 steps per 2048 columns;
 //   - weight fragments (B operand: lane l holds column l & 15, the 8 consecutive k's of chunk l >> 4
 //     of each step) are read straight from global memory, one 16-byte load per step, all issued up
-//     front; they stay in registers when cols <= 2048 (SINGLE) and are re-read per row pair (from
-//     cache) otherwise;
-//   - the rows of h pass in pairs of 16-row tiles.  Reading A fragments straight from global memory
-//     would touch 16 rows x 64 bytes per instruction, all 4 KB apart (one cache channel); instead each
-//     wave loads its own K-slices row by row (one row = 8 x 128 contiguous bytes per instruction),
-//     transposes them through its private slice of LDS into fragment order, and prefetches the next
-//     pair's rows while the matrix cores work on this one.  LDS slot (tile, lane of the load) holds
-//     16 rows x 16 bytes and is padded to 272 bytes so that 16 consecutive lanes hit all banks;
+//     front; they stay in registers when cols <= 2048 (SINGLE) and are re-read per tile (from cache)
+//     otherwise;
+//   - reading A fragments straight from global memory would touch 16 rows x 64 bytes per instruction,
+//     all 4 KB apart (one cache channel); instead each wave loads its own K-slices of a tile row by
+//     row (one row = 8 x 128 contiguous bytes per instruction), transposes them through its private
+//     slice of LDS into fragment order, and has the next tile's rows in flight while the matrix cores
+//     work on this one.  LDS slot (lane of the load) holds 16 rows x 16 bytes and is padded to 272
+//     bytes so that 16 consecutive lanes hit all banks.  74 KB of LDS per workgroup: two fit a CU, and
+//     one's staging overlaps the other's multiplies;
 //   - rows beyond the batch re-read the last row and are never stored;
-//   - per pair the 4 waves' partial tiles are summed through LDS in a fixed order; lane l of a tile
+//   - per tile the 4 waves' partial sums meet in LDS and are added in a fixed order; lane l of a tile
 //     holds column (l & 15), rows 4 * (l >> 4) .. + 3.
-// The pair loop is deliberately not unrolled: a kernel this short runs its code once, so code size
-// is instruction-fetch time.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMmSteps = 16;        // K-steps per wave per super-chunk (4 waves x 16 steps x 32 = 2048 columns)
 constexpr int kMmSlotBytes = 272;   // 16 rows x 16 B + 16 B of padding
-constexpr int kMmWaveLds = 2 * 64 * kMmSlotBytes;   // one wave's staging area: 2 tiles x 64 slots
+constexpr int kMmWaveLds = 64 * kMmSlotBytes;   // one wave's staging area: one tile, 64 slots
+constexpr int kMmMaxRowGroups = 4;
 
 // k offset of the 16-byte chunk that lane `l` of wave `wave` loads from a row (super-chunk at step s0);
 // the same chunk is fragment step l >> 2, k-chunk l & 3 of that wave.
@@ -630,113 +633,137 @@ __device__ __forceinline__ void mm_load_w(const bf16_t* wrow, int cols, int s0, 
     }
 }
 
-// the 32 rows of a pair, this wave's K-slices: one row per instruction
+// the 16 rows of a tile, this wave's K-slices: one row per instruction
 template <bool FULL, bool AL>
 __device__ __forceinline__ void mm_load_h(const bf16_t* h, int rows, int cols, int r0, int s0, int wave, int lane, unsigned (*g)[4]) {
     const int k0 = mm_k0(s0, wave, lane);
     const int koff = (FULL || k0 < cols) ? k0 : 0;      // an out-of-range chunk meets a zero weight fragment
 #pragma unroll
-    for (int r = 0; r < 32; r++) {
+    for (int r = 0; r < 16; r++) {
         const int R = r0 + r < rows ? r0 + r : rows - 1;
         load_vec<bf16_t, 16, AL, false>(h + (size_t)R * cols + koff, g[r]);
     }
 }
 
-template <bool FULL>
-__device__ __forceinline__ void mm_stage_and_multiply(char* lds /* this wave's */, int lane, const unsigned (*g)[4],
-                                                      const unsigned (*wf)[4], const bool* ok, f32x4* acc) {
-    // LDS operations of one wave execute in order: these writes cannot overtake the previous pair's reads
+// LDS operations of one wave execute in order: these writes cannot overtake the previous tile's reads
+__device__ __forceinline__ void mm_stage(char* lds /* this wave's */, int lane, const unsigned (*g)[4]) {
 #pragma unroll
-    for (int r = 0; r < 32; r++) {
+    for (int r = 0; r < 16; r++) {
         v4u t;
         t.x = g[r][0]; t.y = g[r][1]; t.z = g[r][2]; t.w = g[r][3];
-        *reinterpret_cast<v4u*>(lds + ((r >> 4) * 64 + lane) * kMmSlotBytes + (r & 15) * 16) = t;
+        *reinterpret_cast<v4u*>(lds + lane * kMmSlotBytes + r * 16) = t;
     }
-    // all 32 fragment reads first, then the MFMAs: left alone, the scheduler pairs each read with its
+}
+
+template <bool FULL>
+__device__ __forceinline__ void mm_multiply(const char* lds, int lane, const unsigned (*wf)[4], const bool* ok, f32x4& acc) {
+    // all 16 fragment reads first, then the MFMAs: left alone, the scheduler pairs each read with its
     // use and the loop pays one LDS latency per fragment
-    v4u a[2][kMmSteps];
+    v4u a[kMmSteps];
 #pragma unroll
     for (int i = 0; i < kMmSteps; i++)
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++)
-            a[tt][i] = *reinterpret_cast<const v4u*>(lds + (tt * 64 + i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
+        a[i] = *reinterpret_cast<const v4u*>(lds + (i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kMmSteps; i++) {
         v4u b;
         b.x = wf[i][0]; b.y = wf[i][1]; b.z = wf[i][2]; b.w = wf[i][3];
         if (!FULL && !ok[i]) b = v4u{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++)
-            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[tt][i]), __builtin_bit_cast(bf16x8, b), acc[tt], 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
     }
 }
 
+// sum the 4 waves' partial tiles in a fixed order and store rows r0 .. r0 + 15 of the 16 columns at j0
+__device__ __forceinline__ void mm_reduce_store(float* red, f32x4 acc, bf16_t* y, int rows, int n, int r0, int j0, int wave, int lane) {
+    // A matrix-core result may not be read by an LDS write until the instruction has drained (up to
+    // 19 wait states for the longest forms).  The compiler inserts those itself inside a block, but
+    // it was seen to omit them when the last multiply of a K loop and this write sit in different
+    // blocks (loop exit): the write then stored a stale accumulator.  32 idle cycles, tied to `acc`
+    // so that they stay between the two, make it independent of that.
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(acc));
+    float* dst = red + ((size_t)wave * 64 + lane) * 4;
+    dst[0] = acc.x; dst[1] = acc.y; dst[2] = acc.z; dst[3] = acc.w;
+    __syncthreads();
+    if (wave == 0) {
+        const int j = j0 + (lane & 15);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const float p0 = red[((size_t)0 * 64 + lane) * 4 + e], p1 = red[((size_t)1 * 64 + lane) * 4 + e];
+            const float p2 = red[((size_t)2 * 64 + lane) * 4 + e], p3 = red[((size_t)3 * 64 + lane) * 4 + e];
+            const int r = r0 + (lane >> 4) * 4 + e;
+            if (r < rows && j < n) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
+        }
+    }
+    __syncthreads();      // `red` is free again
+}
+
 template <bool FULL, bool SINGLE, bool AL>
-__device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols,
-                                               char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][2 tiles][64 lanes][4] */) {
+__device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols, int row_groups,
+                                               char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rc = lane & 15, kq = lane >> 4;
-    const int j0 = blockIdx.x * 16;
+    const int ncb = (n + 15) / 16;
+    const int cb = blockIdx.x % ncb, rg = blockIdx.x / ncb;
+    const int ntiles = (rows + 15) / 16, per = (ntiles + row_groups - 1) / row_groups;
+    const int t0 = rg * per, t1 = (t0 + per < ntiles) ? t0 + per : ntiles;
+    if (t0 >= t1) return;                                  // whole workgroup: nothing waits on it
+    const int j0 = cb * 16;
     const bf16_t* wrow = W + (size_t)((j0 + rc < n) ? j0 + rc : n - 1) * cols;
     char* lds = stage + wave * kMmWaveLds;
-    unsigned wf[kMmSteps][4], g[32][4];
+    unsigned wf[kMmSteps][4], g[16][4];
     bool ok[kMmSteps];
     if constexpr (SINGLE) {
-        mm_load_w<FULL, AL, true>(wrow, cols, 0, wave, kq, wf, ok);   // streamed once: non-temporal
-        mm_load_h<FULL, AL>(h, rows, cols, 0, 0, wave, lane, g);
-    }
+        // The h rows (from L2) are asked for before the weights (from HBM): loads return in order, so
+        // the tile is staged and its fragments are read back while the weights are still on their way.
+        // Straight-line code up to the first multiply, in two copies (one tile / several): then the
+        // compiler counts exactly how many loads each wait must cover, and with several tiles the next
+        // one's rows stay in flight across the multiplies.
+        mm_load_h<FULL, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
+        mm_load_w<FULL, AL, false>(wrow, cols, 0, wave, kq, wf, ok);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        mm_stage(lds, lane, g);
+        if (t1 - t0 == 1) {
+            mm_multiply<FULL>(lds, lane, wf, ok, acc);
+            mm_reduce_store(red, acc, y, rows, n, t0 * 16, j0, wave, lane);
+            return;
+        }
+        mm_load_h<FULL, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
+        mm_multiply<FULL>(lds, lane, wf, ok, acc);
+        mm_reduce_store(red, acc, y, rows, n, t0 * 16, j0, wave, lane);
 #pragma unroll 1
-    for (int r0 = 0; r0 < rows; r0 += 32) {
-        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        if constexpr (SINGLE) {
-            unsigned gnow[32][4];
-#pragma unroll
-            for (int r = 0; r < 32; r++)
-#pragma unroll
-                for (int e = 0; e < 4; e++) gnow[r][e] = g[r][e];
-            if (r0 + 32 < rows) mm_load_h<FULL, AL>(h, rows, cols, r0 + 32, 0, wave, lane, g);   // prefetch the next pair
-            mm_stage_and_multiply<FULL>(lds, lane, gnow, wf, ok, acc);
-        } else {
+        for (int t = t0 + 1; t < t1; t++) {
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            mm_stage(lds, lane, g);
+            if (t + 1 < t1) mm_load_h<FULL, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
+            mm_multiply<FULL>(lds, lane, wf, ok, acc);
+            mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
+        }
+    } else {
+#pragma unroll 1
+        for (int t = t0; t < t1; t++) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
             for (int s0 = 0; s0 * 32 < cols; s0 += 4 * kMmSteps) {
                 mm_load_w<FULL, AL, false>(wrow, cols, s0, wave, kq, wf, ok);
-                mm_load_h<FULL, AL>(h, rows, cols, r0, s0, wave, lane, g);
-                mm_stage_and_multiply<FULL>(lds, lane, g, wf, ok, acc);
+                mm_load_h<FULL, AL>(h, rows, cols, t * 16, s0, wave, lane, g);
+                mm_stage(lds, lane, g);
+                mm_multiply<FULL>(lds, lane, wf, ok, acc);
             }
+            mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
         }
-        // sum the 4 waves' partial tiles in a fixed order and store
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++) {
-            float* dst = red + ((size_t)(wave * 2 + tt) * 64 + lane) * 4;
-            dst[0] = acc[tt].x; dst[1] = acc[tt].y; dst[2] = acc[tt].z; dst[3] = acc[tt].w;
-        }
-        __syncthreads();
-        if (wave < 2) {      // wave 0 finishes tile 0 of the pair, wave 1 tile 1
-            const int tt = wave;
-            const int j = j0 + rc;
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const float p0 = red[((size_t)(0 * 2 + tt) * 64 + lane) * 4 + e], p1 = red[((size_t)(1 * 2 + tt) * 64 + lane) * 4 + e];
-                const float p2 = red[((size_t)(2 * 2 + tt) * 64 + lane) * 4 + e], p3 = red[((size_t)(3 * 2 + tt) * 64 + lane) * 4 + e];
-                const int r = r0 + tt * 16 + kq * 4 + e;
-                if (r < rows && j < n) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
-            }
-        }
-        __syncthreads();      // `red` is free again
     }
 }
 
 template <int IND, bool FULL, bool SINGLE>
-__global__ __launch_bounds__(kBlock) void k_gemm_mfma_bf16(GemvArgs p) {
+__global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
     const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
     const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
     bf16_t* y = static_cast<bf16_t*>(p.out);
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
-    __shared__ float red[4 * 2 * 64 * 4];
+    __shared__ float red[4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);   // rows keep the alignment: cols is a multiple of 8
-    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, stage, red);
-    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, stage, red);
+    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
 // ---- batched multi-tensor copy -----------------------------------------------------------------
@@ -930,7 +957,10 @@ bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     if constexpr (sizeof(T) == 2) {
         if (rows > 8 && cols % 8 == 0) {   // a dense contraction: matrix cores (up to 8 rows the vector form below is faster)
             out->block = dim3(kBlock);
-            out->grid = dim3(blocks_for(n, 16));
+            // row groups of 16-row tiles: enough workgroups to fill the chip twice over at most
+            const int ntiles = (rows + 15) / 16;
+            out->gemm_row_groups = (unsigned)(ntiles < kMmMaxRowGroups ? ntiles : kMmMaxRowGroups);
+            out->grid = dim3(blocks_for(n, 16) * out->gemm_row_groups);
             constexpr int kSuper = 32 * 4 * kMmSteps;   // columns one pass of the 4 waves covers
             if (cols == kSuper) out->fn = gemm_by_ind<true, true>(ind);
             else if (cols < kSuper) out->fn = gemm_by_ind<false, true>(ind);
@@ -1000,6 +1030,7 @@ bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out) {
     default: return false;
     }
     out->mod_fn = nullptr;
+    out->gemm_row_groups = 0;
     if (dtype == kF32) return plan_t<float>(op, ind_mask, shape, out);
     if (dtype == kBF16) return plan_t<bf16_t>(op, ind_mask, shape, out);
     return false;
