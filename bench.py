@@ -208,6 +208,10 @@ def main() -> int:
         from pg_workloads import bf16_bits_to_f32
         gf, of = bf16_bits_to_f32(g).astype(np.float64), bf16_bits_to_f32(o).astype(np.float64)
         cpu["rel_l2_gpu_vs_oracle"] = float(np.sqrt(((gf - of) ** 2).sum() / (of ** 2).sum()))
+        # elements whose bf16 patterns differ, and the largest |g - o| / max(|o|, rms(o)) (the bf16 bound is 2e-2)
+        rms = float(np.sqrt(np.mean(of * of)))
+        cpu["elements_differing"] = int((g != o).sum())
+        cpu["max_err_over_scale"] = float((np.abs(gf - of) / np.maximum(np.abs(of), rms)).max())
         log(f"[bench] oracle: {cpu_us / 1e3:.1f} ms/iteration on {cpu['cores']} threads; GPU vs oracle rel L2 {cpu['rel_l2_gpu_vs_oracle']:.2e}")
 
     step_us = sum(us.values())

@@ -122,7 +122,14 @@ def main() -> int:
                 del mats, vec
             print(json.dumps({"config": 6, "workload": "batch-1 bf16 GEMV size sweep, 24 launches per graph", "gemv": rows_out}), flush=True)
             continue
-        if cfg == 0:
+        if cfg == 7:
+            # the decode chain read literally: 24 layers x one (RMSNorm, GEMV, GELU, add) = 96 kernels,
+            # with 24 external inputs (23 input adds): 119 kernels per iteration
+            from pg_workloads import decode_chain
+            spec = decode_chain(blocks_per_layer=1, n_ext=24)
+            w = [to_device(a) for a in make_weights(spec)]
+            chain, r = time_chain(pg, torch, spec, w, device_sets(spec, 3), args.iters, 10, stream)
+        elif cfg == 0:
             # launch floor: 512 dependent kernels on 64 elements each, so the time per kernel is the
             # cost of dispatching one dependent kernel (host launch for eager, graph node for replay)
             spec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")

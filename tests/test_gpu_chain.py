@@ -177,3 +177,23 @@ def test_refresh_stress_reduced():
         want = oracle.run_chain(spec, h.w_np, x_np, 0, k + 1)[kk.out][:kk.n]
         assert_close(h.chain.output(kk.out)[:kk.n], want, "bf16", f"kernel {k}")
     h.close()
+
+
+def test_selected_is_as_fast_as_the_best_single_mode():
+    """Sec. 4.3: the selected mixture is at least as good as the best of its candidates.  A timing
+    check, so with a wide margin: config 1 (launch-bound: a graph should win) and a large-tensor chain
+    (graphs cannot win; copying the input must lose)."""
+    for spec, w in ((elementwise_chain(), None), (large_tensor_chain(n_kernels=12, shape=(8, 64, 56, 56), n_segments=3), None)):
+        h = Harness(spec)
+        sets = [h.inputs(t)[1] for t in range(3)]
+        h._keep = sets
+        cost = h.chain.profile(sets[0], h.stream, iters=9, inner=3)
+        sel = pg.select(cost)
+        us = {}
+        for name, mode, modes in (("eager", pg.EAGER, None), ("copy", pg.GRAPH_COPY, None), ("indirect", pg.GRAPH_INDIRECT, None),
+                                  ("selected", pg.SELECTED, sel)):
+            h.chain.time_loop(mode, sets, 10, h.stream, modes)
+            us[name] = min(h.chain.time_loop(mode, sets, 50, h.stream, modes) for _ in range(3))
+        say(f"{spec.name}: {us} selected {sel.tolist()}")
+        assert us["selected"] <= 1.25 * min(us["eager"], us["copy"], us["indirect"]), us
+        h.close()

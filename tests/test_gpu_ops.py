@@ -128,7 +128,9 @@ def test_rmsnorm(dtype, rows, cols, off):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("rows,n,cols", [(1, 5, 24), (1, 2048, 2048), (5, 33, 520), (3, 7, 13), (9, 64, 4096), (1, 130, 2056),
-                                         (17, 16, 64), (2, 100, 2048), (130, 40, 2048), (128, 256, 2048), (33, 50, 8), (16, 31, 6152)])
+                                         (17, 16, 64), (2, 100, 2048), (130, 40, 2048), (128, 256, 2048), (33, 50, 8), (16, 31, 6152),
+                                         # matrix-core form: several row groups, several K passes, ragged last tile and column block
+                                         (40, 48, 4096), (100, 33, 2048), (64, 2048, 2048), (20, 16, 2056), (72, 24, 8200), (8, 64, 2048)])
 def test_gemv(dtype, rows, n, cols):
     say(f"gemv {dtype} rows={rows} n={n} cols={cols}")
     rng = np.random.Generator(np.random.PCG64(300 + cols + n))
