@@ -137,7 +137,8 @@ pg_status pg_chain_build(const pg_kernel_desc *kernels, int32_t n_kernels,
  * its kernels on `hip_stream` twice -- once reading the static placeholders, once reading the
  * pointer table -- instantiate and upload the graphs, and write the static part of the copy
  * kernel's job list into the workspace.  Synchronises the stream before returning.  Calling it
- * again re-captures. */
+ * again re-captures: it first waits for `hip_stream` (replays issued on another stream must have
+ * been waited for by the caller) and destroys the old graphs. */
 pg_status pg_capture(pg_chain *chain, void *hip_stream);
 
 /* One iteration, kernel by kernel from the host with the caller's pointers (the no-graph
@@ -220,6 +221,8 @@ pg_status pg_chain_pointer_table(const pg_chain *chain, void **dev_ptr_out, size
 pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);
 pg_status pg_set_table_refresh(pg_chain *chain, int32_t how /* pg_table_refresh */);
 pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */);
+/* Destroys the graphs and host objects.  The caller has synchronised every stream the chain ran on;
+ * device memory stays the caller's.  NULL is allowed. */
 void pg_chain_destroy(pg_chain *chain);
 
 const char *pg_last_error(void);

@@ -203,6 +203,9 @@ class Chain:
     # -- lifetime
     def close(self):
         if getattr(self, "_h", None):
+            if self.workspace is not None:
+                # pg_chain_destroy wants every stream the chain ran on idle: nothing may still replay its graphs
+                _torch().cuda.synchronize(self.workspace.device)
             lib().pg_chain_destroy(self._h)
             self._h = None
 

@@ -647,6 +647,7 @@ pg_status pg_capture(pg_chain* c, void* hip_stream) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     PG_HIP(hipStreamIsCapturing(s, &cs));
     if (cs != hipStreamCaptureStatusNone) return fail(PG_EINVAL, "the stream is already capturing");
+    if (c->captured) PG_HIP(hipStreamSynchronize(s));   // a replay of the old graphs may still be running on this stream
     destroy_graphs(c);
     // static side of the copy kernel's job lists
     for (auto& L : c->copy_lists) {

@@ -955,7 +955,7 @@ template <typename T>
 bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     constexpr int NV = 16 / (int)sizeof(T);
     if constexpr (sizeof(T) == 2) {
-        if (rows > 8 && cols % 8 == 0) {   // a dense contraction: matrix cores (up to 8 rows the vector form below is faster)
+        if (rows > 4 && cols % 8 == 0) {   // a dense contraction: matrix cores (up to 4 rows the vector form below is faster)
             out->block = dim3(kBlock);
             // row groups of 16-row tiles: enough workgroups to fill the chip twice over at most
             const int ntiles = (rows + 15) / 16;
