@@ -596,15 +596,14 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
 //     the weights in its L2;
 //   - its 4 waves split K: of every 8 consecutive 32-wide K-steps wave w takes steps 2w and 2w+1 (128
 //     contiguous bytes of each row), 16 steps per 2048 columns;
-//   - weight fragments (B operand: lane l holds column l & 15, the 8 consecutive k's of chunk l >> 4
-//     of each step) are read straight from global memory, one 16-byte load per step, all issued up
-//     front; they stay in registers when cols <= 2048 (SINGLE) and are re-read per tile (from cache)
-//     otherwise;
-//   - reading A fragments straight from global memory would touch 16 rows x 64 bytes per instruction,
-//     all 4 KB apart (one cache channel); instead each wave loads its own K-slices of a tile row by
-//     row (one row = 8 x 128 contiguous bytes per instruction), transposes them through its private
-//     slice of LDS into fragment order, and has the next tile's rows in flight while the matrix cores
-//     work on this one.  LDS slot (lane of the load) holds 16 rows x 16 bytes and is padded to 272
+//   - a fragment (A: lane l holds row l & 15, B: column l & 15; the 8 consecutive k's of chunk l >> 4
+//     of a step) read straight from global memory would touch 16 rows x 64 bytes per instruction, all
+//     4 KB apart: half cache lines, one cache channel (measured: 0.3 - 1.1 us slower per launch).
+//     Instead each wave loads its own K-slices of 16 rows -- a tile of h, or the weights of the 16
+//     columns -- row by row (one row = 8 x 128 contiguous bytes per instruction) and transposes them
+//     through its private slice of LDS into fragment order.  The weight fragments stay in registers
+//     when cols <= 2048 (SINGLE) and are re-read per tile (from cache) otherwise; the next tile's rows
+//     of h are in flight while the matrix cores work on this one.  LDS slot (lane of the load) holds 16 rows x 16 bytes and is padded to 272
 //     bytes so that 16 consecutive lanes hit all banks.  74 KB of LDS per workgroup: two fit a CU, and
 //     one's staging overlaps the other's multiplies;
 //   - rows beyond the batch re-read the last row and are never stored;
@@ -623,19 +622,10 @@ __device__ __forceinline__ int mm_k0(int s0, int wave, int l) {
     return (s0 + (l >> 3) * 8 + wave * 2 + ((l >> 2) & 1)) * 32 + (l & 3) * 8;
 }
 
-template <bool FULL, bool AL, bool NT>
-__device__ __forceinline__ void mm_load_w(const bf16_t* wrow, int cols, int s0, int wave, int kq, unsigned (*wf)[4], bool* ok) {
-#pragma unroll
-    for (int i = 0; i < kMmSteps; i++) {
-        const int k0 = (s0 + (i >> 1) * 8 + wave * 2 + (i & 1)) * 32 + kq * 8;
-        ok[i] = FULL || k0 < cols;                      // cols is a multiple of 8: a chunk is all in or all out
-        load_vec<bf16_t, 16, AL, NT>(wrow + (ok[i] ? k0 : 0), wf[i]);
-    }
-}
-
-// the 16 rows of a tile, this wave's K-slices: one row per instruction
+// 16 rows of a row-major matrix (a tile of h, or the weights of 16 output columns), this wave's
+// K-slices: one row per instruction; rows beyond the matrix repeat its last row
 template <bool FULL, bool AL>
-__device__ __forceinline__ void mm_load_h(const bf16_t* h, int rows, int cols, int r0, int s0, int wave, int lane, unsigned (*g)[4]) {
+__device__ __forceinline__ void mm_load_rows(const bf16_t* h, int rows, int cols, int r0, int s0, int wave, int lane, unsigned (*g)[4]) {
     const int k0 = mm_k0(s0, wave, lane);
     const int koff = (FULL || k0 < cols) ? k0 : 0;      // an out-of-range chunk meets a zero weight fragment
 #pragma unroll
@@ -655,22 +645,25 @@ __device__ __forceinline__ void mm_stage(char* lds /* this wave's */, int lane, 
     }
 }
 
-template <bool FULL>
-__device__ __forceinline__ void mm_multiply(const char* lds, int lane, const unsigned (*wf)[4], const bool* ok, f32x4& acc) {
-    // all 16 fragment reads first, then the MFMAs: left alone, the scheduler pairs each read with its
-    // use and the loop pays one LDS latency per fragment
-    v4u a[kMmSteps];
+// fragment (step i, k-chunk lane >> 4, row or column lane & 15) of the tile staged in `lds`
+__device__ __forceinline__ void mm_read_frags(const char* lds, int lane, v4u* f) {
 #pragma unroll
     for (int i = 0; i < kMmSteps; i++)
-        a[i] = *reinterpret_cast<const v4u*>(lds + (i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
-    __builtin_amdgcn_sched_barrier(0);
+        f[i] = *reinterpret_cast<const v4u*>(lds + (i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
+}
+// chunks beyond cols: the weight side is zeroed, the h side may then hold anything
+template <bool FULL>
+__device__ __forceinline__ void mm_zero_tail(v4u* b, int cols, int s0, int wave, int kq) {
+    if constexpr (!FULL) {
 #pragma unroll
-    for (int i = 0; i < kMmSteps; i++) {
-        v4u b;
-        b.x = wf[i][0]; b.y = wf[i][1]; b.z = wf[i][2]; b.w = wf[i][3];
-        if (!FULL && !ok[i]) b = v4u{0u, 0u, 0u, 0u};
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+        for (int i = 0; i < kMmSteps; i++)      // cols is a multiple of 8: a chunk is all in or all out
+            if ((s0 + (i >> 1) * 8 + wave * 2 + (i & 1)) * 32 + kq * 8 >= cols) b[i] = v4u{0u, 0u, 0u, 0u};
     }
+}
+__device__ __forceinline__ void mm_mfma(const v4u* a, const v4u* b, f32x4& acc) {
+#pragma unroll
+    for (int i = 0; i < kMmSteps; i++)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[i]), acc, 0, 0, 0);
 }
 
 // sum the 4 waves' partial tiles in a fixed order and store rows r0 .. r0 + 15 of the 16 columns at j0
@@ -701,41 +694,42 @@ template <bool FULL, bool SINGLE, bool AL>
 __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols, int row_groups,
                                                char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int rc = lane & 15, kq = lane >> 4;
+    const int kq = lane >> 4;
     const int ncb = (n + 15) / 16;
     const int cb = blockIdx.x % ncb, rg = blockIdx.x / ncb;
     const int ntiles = (rows + 15) / 16, per = (ntiles + row_groups - 1) / row_groups;
     const int t0 = rg * per, t1 = (t0 + per < ntiles) ? t0 + per : ntiles;
     if (t0 >= t1) return;                                  // whole workgroup: nothing waits on it
     const int j0 = cb * 16;
-    const bf16_t* wrow = W + (size_t)((j0 + rc < n) ? j0 + rc : n - 1) * cols;
     char* lds = stage + wave * kMmWaveLds;
-    unsigned wf[kMmSteps][4], g[16][4];
-    bool ok[kMmSteps];
+    unsigned g[16][4], gw[16][4];
+    v4u a[kMmSteps], b[kMmSteps];
     if constexpr (SINGLE) {
         // The h rows (from L2) are asked for before the weights (from HBM): loads return in order, so
-        // the tile is staged and its fragments are read back while the weights are still on their way.
-        // Straight-line code up to the first multiply, in two copies (one tile / several): then the
-        // compiler counts exactly how many loads each wait must cover, and with several tiles the next
-        // one's rows stay in flight across the multiplies.
-        mm_load_h<FULL, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
-        mm_load_w<FULL, AL, false>(wrow, cols, 0, wave, kq, wf, ok);
+        // the tile is staged and its fragments are back in registers while the weights are still on
+        // their way; then the same LDS slice takes the weights.  The weight fragments stay in registers
+        // for all tiles of the workgroup, and a later tile's rows are in flight across the multiplies
+        // of the one before.
+        mm_load_rows<FULL, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
+        mm_load_rows<FULL, AL>(W, n, cols, j0, 0, wave, lane, gw);
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         mm_stage(lds, lane, g);
-        if (t1 - t0 == 1) {
-            mm_multiply<FULL>(lds, lane, wf, ok, acc);
-            mm_reduce_store(red, acc, y, rows, n, t0 * 16, j0, wave, lane);
-            return;
-        }
-        mm_load_h<FULL, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
-        mm_multiply<FULL>(lds, lane, wf, ok, acc);
+        mm_read_frags(lds, lane, a);
+        if (t1 - t0 > 1) mm_load_rows<FULL, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
+        mm_stage(lds, lane, gw);
+        mm_read_frags(lds, lane, b);
+        mm_zero_tail<FULL>(b, cols, 0, wave, kq);
+        __builtin_amdgcn_sched_barrier(0);   // all fragment reads before the first multiply, not one LDS latency per pair
+        mm_mfma(a, b, acc);
         mm_reduce_store(red, acc, y, rows, n, t0 * 16, j0, wave, lane);
 #pragma unroll 1
         for (int t = t0 + 1; t < t1; t++) {
             acc = f32x4{0.f, 0.f, 0.f, 0.f};
             mm_stage(lds, lane, g);
-            if (t + 1 < t1) mm_load_h<FULL, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
-            mm_multiply<FULL>(lds, lane, wf, ok, acc);
+            if (t + 1 < t1) mm_load_rows<FULL, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
+            mm_read_frags(lds, lane, a);
+            __builtin_amdgcn_sched_barrier(0);
+            mm_mfma(a, b, acc);
             mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
         }
     } else {
@@ -744,10 +738,15 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
             for (int s0 = 0; s0 * 32 < cols; s0 += 4 * kMmSteps) {
-                mm_load_w<FULL, AL, false>(wrow, cols, s0, wave, kq, wf, ok);
-                mm_load_h<FULL, AL>(h, rows, cols, t * 16, s0, wave, lane, g);
+                mm_load_rows<FULL, AL>(h, rows, cols, t * 16, s0, wave, lane, g);
+                mm_load_rows<FULL, AL>(W, n, cols, j0, s0, wave, lane, gw);
                 mm_stage(lds, lane, g);
-                mm_multiply<FULL>(lds, lane, wf, ok, acc);
+                mm_read_frags(lds, lane, a);
+                mm_stage(lds, lane, gw);
+                mm_read_frags(lds, lane, b);
+                mm_zero_tail<FULL>(b, cols, s0, wave, kq);
+                __builtin_amdgcn_sched_barrier(0);
+                mm_mfma(a, b, acc);
             }
             mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
         }
