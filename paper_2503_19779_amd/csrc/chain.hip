@@ -4,7 +4,9 @@
 // one for eager launches (external operands patched with the caller's pointers on every call),
 // one whose external operands are static placeholders (graph + copy refresh), and one whose
 // external operands are pointer-table slots (graph + Parameter Indirection).  Graphs are made by
-// stream capture, once per segment and per graph mode.
+// stream capture, once per segment and per graph mode.  A fourth block serves the graphs whose
+// kernel nodes are rewritten from the host before each launch (pg_replay_update); those graphs are
+// built node by node, so that the runtime keeps a handle on every node.
 #include "../../include/pygraph_hip.h"
 #include "kernels.h"
 

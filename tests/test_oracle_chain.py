@@ -148,3 +148,20 @@ def test_select_properties():
         oracle.select(np.array([[1.0, 2.0, 3.0], [math.nan, math.inf, math.nan]]))
     for _ in range(50):
         assert np.array_equal(oracle.select(cost), sel)                   # deterministic
+
+
+def test_result_does_not_depend_on_the_thread_count():
+    """The oracle is parallel only across independent outputs, each summed in a fixed order: one
+    thread and all threads give the same bits (so the timed oracle is the checked oracle)."""
+    spec = decode_chain(batch=3, layers=2, blocks_per_layer=2, hidden=264, n_ext=3)
+    w, x = make_weights(spec), make_inputs(spec, 0)
+    n_max = oracle.max_threads()
+    try:
+        oracle.set_threads(1)
+        one = oracle.run_chain(spec, w, x)
+        oracle.set_threads(max(2, n_max))
+        many = oracle.run_chain(spec, w, x)
+    finally:
+        oracle.set_threads(n_max)
+    for a, b in zip(one, many):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
