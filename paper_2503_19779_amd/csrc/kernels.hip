@@ -615,6 +615,7 @@ constexpr int kMmSteps = 16;        // K-steps per wave per super-chunk (4 waves
 constexpr int kMmSlotBytes = 272;   // 16 rows x 16 B + 16 B of padding
 constexpr int kMmWaveLds = 64 * kMmSlotBytes;   // one wave's staging area: one tile, 64 slots
 constexpr int kMmMaxRowGroups = 4;
+constexpr int kMmWideRows = 64;     // rows from which the 32-column form is used
 
 // k offset of the 16-byte chunk that lane `l` of wave `wave` loads from a row (super-chunk at step s0);
 // the same chunk is fragment step l >> 2, k-chunk l & 3 of that wave.
@@ -751,6 +752,78 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
             mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
         }
     }
+}
+
+// Wide form for many rows and cols == 2048: 32 output columns per workgroup, i.e. two sets of weight
+// fragments and two accumulators against every staged tile of h, which halves the h traffic per
+// output (the bound once rows >= 64).  One workgroup per CU (the fragments of 32 columns do not fit
+// the register budget of two), waves 0 and 1 each finish one 16-column half.
+template <bool AL>
+__device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols, int row_groups,
+                                                    char* stage, float* red /* LDS: [2 halves][4 waves][64 lanes][4] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ncb = (n + 31) / 32;
+    const int cb = blockIdx.x % ncb, rg = blockIdx.x / ncb;
+    const int ntiles = (rows + 15) / 16, per = (ntiles + row_groups - 1) / row_groups;
+    const int t0 = rg * per, t1 = (t0 + per < ntiles) ? t0 + per : ntiles;
+    if (t0 >= t1) return;
+    const int j0 = cb * 32;
+    char* lds = stage + wave * kMmWaveLds;
+    unsigned g[16][4], gw0[16][4], gw1[16][4];
+    v4u a[kMmSteps], b0[kMmSteps], b1[kMmSteps];
+    mm_load_rows<true, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
+    mm_load_rows<true, AL>(W, n, cols, j0, 0, wave, lane, gw0);
+    mm_load_rows<true, AL>(W, n, cols, j0 + 16, 0, wave, lane, gw1);
+    mm_stage(lds, lane, g);
+    mm_read_frags(lds, lane, a);
+    if (t1 - t0 > 1) mm_load_rows<true, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
+    mm_stage(lds, lane, gw0);
+    mm_read_frags(lds, lane, b0);
+    mm_stage(lds, lane, gw1);
+    mm_read_frags(lds, lane, b1);
+    for (int t = t0;;) {
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kMmSteps; i++) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b0[i]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b1[i]), acc1, 0, 0, 0);
+        }
+        asm volatile("s_nop 15\n\ts_nop 15" : "+v"(acc0), "+v"(acc1));   // see mm_reduce_store
+        float* d0 = red + ((size_t)(0 * 4 + wave) * 64 + lane) * 4;
+        float* d1 = red + ((size_t)(1 * 4 + wave) * 64 + lane) * 4;
+        d0[0] = acc0.x; d0[1] = acc0.y; d0[2] = acc0.z; d0[3] = acc0.w;
+        d1[0] = acc1.x; d1[1] = acc1.y; d1[2] = acc1.z; d1[3] = acc1.w;
+        __syncthreads();
+        if (wave < 2) {
+            const float* src = red + (size_t)wave * 4 * 64 * 4;
+            const int j = j0 + wave * 16 + (lane & 15);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float p0 = src[((size_t)0 * 64 + lane) * 4 + e], p1 = src[((size_t)1 * 64 + lane) * 4 + e];
+                const float p2 = src[((size_t)2 * 64 + lane) * 4 + e], p3 = src[((size_t)3 * 64 + lane) * 4 + e];
+                const int r = t * 16 + (lane >> 4) * 4 + e;
+                if (r < rows && j < n) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
+            }
+        }
+        __syncthreads();
+        if (++t >= t1) break;
+        mm_stage(lds, lane, g);
+        if (t + 1 < t1) mm_load_rows<true, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
+        mm_read_frags(lds, lane, a);
+    }
+}
+
+template <int IND>
+__global__ __launch_bounds__(kBlock, 1) void k_gemm_mfma_bf16_wide(GemvArgs p) {
+    const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
+    const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
+    bf16_t* y = static_cast<bf16_t*>(p.out);
+    __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
+    __shared__ float red[2 * 4 * 64 * 4];
+    const bool al = aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemm_mfma_wide_body<true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    else gemm_mfma_wide_body<false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
 template <int IND, bool FULL, bool SINGLE>
@@ -961,7 +1034,16 @@ bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
             out->gemm_row_groups = (unsigned)(ntiles < kMmMaxRowGroups ? ntiles : kMmMaxRowGroups);
             out->grid = dim3(blocks_for(n, 16) * out->gemm_row_groups);
             constexpr int kSuper = 32 * 4 * kMmSteps;   // columns one pass of the 4 waves covers
-            if (cols == kSuper) out->fn = gemm_by_ind<true, true>(ind);
+            if (cols == kSuper && rows >= kMmWideRows && n >= 32) {
+                out->grid = dim3(blocks_for(n, 32) * out->gemm_row_groups);
+                switch (ind) {
+                case 0: out->fn = PG_FN(k_gemm_mfma_bf16_wide<0>); break;
+                case 1: out->fn = PG_FN(k_gemm_mfma_bf16_wide<1>); break;
+                case 2: out->fn = PG_FN(k_gemm_mfma_bf16_wide<2>); break;
+                case 3: out->fn = PG_FN(k_gemm_mfma_bf16_wide<3>); break;
+                default: out->fn = nullptr;
+                }
+            } else if (cols == kSuper) out->fn = gemm_by_ind<true, true>(ind);
             else if (cols < kSuper) out->fn = gemm_by_ind<false, true>(ind);
             else if (cols % kSuper == 0) out->fn = gemm_by_ind<true, false>(ind);
             else out->fn = gemm_by_ind<false, false>(ind);
