@@ -122,6 +122,27 @@ def main() -> int:
                 del mats, vec
             print(json.dumps({"config": 6, "workload": "batch-1 bf16 GEMV size sweep, 24 launches per graph", "gemv": rows_out}), flush=True)
             continue
+        if cfg == 8:
+            # The batched GEMV alone at every bucket size: graphs of the decode chain's 120 launches over
+            # its 120 weight matrices (1 GB, so every launch streams its weights from HBM).
+            from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, WEIGHT
+            H = 2048
+            mats = [torch.randn(H * H, device="cuda", dtype=torch.float32).mul_(0.02).to(torch.bfloat16) for _ in range(120)]
+            rows_out = []
+            for B in (1, 2, 4, 8, 16, 32, 64, 128):
+                act = torch.randn(B * H, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                ks = [KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s), Ref(WEIGHT, 120)), H, rows=B, cols=H) for s in range(120)]
+                spec = ChainSpec(f"gemv_b{B}", ks, [], [TensorSpec("bf16", B * H)], [TensorSpec("bf16", H * H)] * 120 + [TensorSpec("bf16", B * H)], [0])
+                chain = pg.Chain(spec, mats + [act])
+                chain.capture(stream)
+                chain.time_loop(pg.GRAPH_COPY, [[]], 5, stream)
+                us = chain.time_loop(pg.GRAPH_COPY, [[]], 20, stream) / 120
+                chain.close()
+                b = H * H * 2 + 2 * B * H * 2
+                rows_out.append({"batch": B, "us_per_launch": us, "GBps": b / us / 1e3, "TFLOPs": 2.0 * B * H * H / us / 1e6})
+                log(f"[configs] GEMV 2048 x 2048, batch {B}: {us:.2f} us per launch, {b / us / 1e3:.0f} GB/s, {2.0 * B * H * H / us / 1e6:.1f} TFLOP/s")
+            print(json.dumps({"config": 8, "workload": "bf16 GEMV 2048 x 2048 at batch 1..128, 120 launches per graph over 120 matrices", "gemv": rows_out}), flush=True)
+            continue
         if cfg == 7:
             # the decode chain read literally: 24 layers x one (RMSNorm, GEMV, GELU, add) = 96 kernels,
             # with 24 external inputs (23 input adds): 119 kernels per iteration
