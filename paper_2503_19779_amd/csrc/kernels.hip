@@ -528,63 +528,73 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
     else gemv_body<T, R, RS, false>(W, h, y, p.n, p.cols, j0, lane);
 }
 
-// Batched (rows > 1): one wave per output column; the weight chunk stays in registers while the
-// rows of h stream past it, kRowBlock rows at a time.
-constexpr int kRowBlock = 4;
-
-template <typename T, int RS, bool AL>
-__device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int rows, int n, int cols, int j, int lane) {
+// Batched (rows > 1) on the vector units: one wave per R output columns, as in the one-row kernel;
+// the R weight chunks stay in registers while the rows of h (from cache) stream past them,
+// RB rows at a time (RB = 2 when there are only two rows: a clamped row would be loaded and summed
+// for nothing).
+template <typename T, int R, int RB, int RS, bool AL>
+__device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int rows, int n, int cols, int j0, int lane) {
     constexpr int NV = Vec<T, 16>::NV;
     const int nfull = cols / NV;
     const int nvec = (cols + NV - 1) / NV;
-    const T* wrow = W + (size_t)j * cols;
-    for (int r0 = 0; r0 < rows; r0 += kRowBlock) {
-        float acc[kRowBlock];
-        const T* hrow[kRowBlock];
+    const T* wrow[R];
 #pragma unroll
-        for (int rr = 0; rr < kRowBlock; rr++) {
-            acc[rr] = 0.f;
+    for (int r = 0; r < R; r++) wrow[r] = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * cols;   // a ragged last group re-reads the last row
+    for (int r0 = 0; r0 < rows; r0 += RB) {
+        float acc[R][RB];
+        const T* hrow[RB];
+#pragma unroll
+        for (int rr = 0; rr < RB; rr++) {
+#pragma unroll
+            for (int r = 0; r < R; r++) acc[r][rr] = 0.f;
             hrow[rr] = h + (size_t)((r0 + rr < rows) ? r0 + rr : rows - 1) * cols;
         }
         for (int v0 = 0; v0 < nvec; v0 += 64 * kGemvChunk) {
-            unsigned ww[kGemvChunk][4], wh[kRowBlock][kGemvChunk][4];
+            unsigned ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4];
             if (RS != 2 || nfull > 0) {
 #pragma unroll
-                for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, false>(wrow, nfull, v0 + u * 64 + lane, ww[u]);
+                for (int r = 0; r < R; r++)
 #pragma unroll
-                for (int rr = 0; rr < kRowBlock; rr++)
+                    for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, true>(wrow[r], nfull, v0 + u * 64 + lane, ww[r][u]);
+#pragma unroll
+                for (int rr = 0; rr < RB; rr++)
 #pragma unroll
                     for (int u = 0; u < kGemvChunk; u++) gemv_issue<T, RS, AL, false>(hrow[rr], nfull, v0 + u * 64 + lane, wh[rr][u]);
             }
 #pragma unroll
-            for (int u = 0; u < kGemvChunk; u++) gemv_fix<T, RS>(wrow, cols, nfull, v0 + u * 64 + lane, ww[u]);
+            for (int r = 0; r < R; r++)
 #pragma unroll
-            for (int rr = 0; rr < kRowBlock; rr++)
+                for (int u = 0; u < kGemvChunk; u++) gemv_fix<T, RS>(wrow[r], cols, nfull, v0 + u * 64 + lane, ww[r][u]);
+#pragma unroll
+            for (int rr = 0; rr < RB; rr++)
 #pragma unroll
                 for (int u = 0; u < kGemvChunk; u++) {
                     gemv_fix<T, RS>(hrow[rr], cols, nfull, v0 + u * 64 + lane, wh[rr][u]);
-                    acc[rr] = dot_acc<T>(ww[u], wh[rr][u], acc[rr]);
+#pragma unroll
+                    for (int r = 0; r < R; r++) acc[r][rr] = dot_acc<T>(ww[r][u], wh[rr][u], acc[r][rr]);
                 }
         }
 #pragma unroll
-        for (int rr = 0; rr < kRowBlock; rr++) {
-            const float s = wave_sum(acc[rr]);
-            if (lane == 0 && r0 + rr < rows) store_elem(y + (size_t)(r0 + rr) * n + j, s);
-        }
+        for (int rr = 0; rr < RB; rr++)
+#pragma unroll
+            for (int r = 0; r < R; r++) {
+                const float s = wave_sum(acc[r][rr]);
+                if (lane == 0 && r0 + rr < rows && j0 + r < n) store_elem(y + (size_t)(r0 + rr) * n + j0 + r, s);
+            }
     }
 }
 
-template <typename T, int IND, int RS>
+template <typename T, int IND, int R, int RB, int RS>
 __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
     const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
     const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
     T* y = static_cast<T*>(p.out);
     const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (j >= p.n) return;
+    const int j0 = (blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * R;
+    if (j0 >= p.n) return;
     const bool al = RS != 2 && aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemvb_body<T, RS, true>(W, h, y, p.rows, p.n, p.cols, j, lane);
-    else gemvb_body<T, RS, false>(W, h, y, p.rows, p.n, p.cols, j, lane);
+    if (al) gemvb_body<T, R, RB, RS, true>(W, h, y, p.rows, p.n, p.cols, j0, lane);
+    else gemvb_body<T, R, RB, RS, false>(W, h, y, p.rows, p.n, p.cols, j0, lane);
 }
 
 // Batched bf16 with whole 16-byte vectors per row: y[rows, n] = h[rows, cols] * W[n, cols]^T is a
@@ -984,13 +994,13 @@ const void* gemv_by_ind(int ind) {
     default: return nullptr;
     }
 }
-template <typename T, int RS>
+template <typename T, int R, int RB, int RS>
 const void* gemvb_by_ind(int ind) {
     switch (ind) {
-    case 0: return PG_FN(k_gemv_batched<T, 0, RS>);
-    case 1: return PG_FN(k_gemv_batched<T, 1, RS>);
-    case 2: return PG_FN(k_gemv_batched<T, 2, RS>);
-    case 3: return PG_FN(k_gemv_batched<T, 3, RS>);
+    case 0: return PG_FN(k_gemv_batched<T, 0, R, RB, RS>);
+    case 1: return PG_FN(k_gemv_batched<T, 1, R, RB, RS>);
+    case 2: return PG_FN(k_gemv_batched<T, 2, R, RB, RS>);
+    case 3: return PG_FN(k_gemv_batched<T, 3, R, RB, RS>);
     default: return nullptr;
     }
 }
@@ -1005,8 +1015,11 @@ bool plan_gemv_rs(int ind, int rows, int n, Launch* out) {
     } else if (rows == 1) {
         out->fn = gemv_by_ind<T, 1, RS>(ind);
         out->grid = dim3(blocks_for(n, kBlock / 64));
+    } else if (n >= 1024) {
+        out->fn = rows == 2 ? gemvb_by_ind<T, 2, 2, RS>(ind) : gemvb_by_ind<T, 2, 4, RS>(ind);
+        out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
     } else {
-        out->fn = gemvb_by_ind<T, RS>(ind);
+        out->fn = rows == 2 ? gemvb_by_ind<T, 1, 2, RS>(ind) : gemvb_by_ind<T, 1, 4, RS>(ind);
         out->grid = dim3(blocks_for(n, kBlock / 64));
     }
     return out->fn != nullptr;
