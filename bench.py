@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--no-copy-bench", action="store_true", help="skip the copy-kernel bandwidth leg (config 3 sizes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-refresh-baselines", action="store_true",
-                    help="skip the two refresh baselines (host-side node updates, per-tensor memcpy); the profiler runs use this")
+                    help="skip the refresh baselines (host-side node updates, per-tensor memcpy, the two alternating table mechanisms); the profiler runs use this")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
     args = ap.parse_args()
@@ -94,8 +94,15 @@ def main() -> int:
     log(f"[bench] graph_indirect with a pinned-memcpy table refresh: {us_ind_memcpy:.1f} us/iteration")
     # the baselines the two refresh designs stand against: the host rewrites the external-reading
     # kernel nodes' arguments before each launch; the copy refresh as one memcpy per tensor
-    us_update = us_copy_memcpy = None
+    us_update = us_copy_memcpy = us_ind_graph_memcpy = us_ind_host_table = None
     if not args.no_refresh_baselines:
+        # the other two ways of getting the pointers to the kernels: a copy node inside the graph, a host-resident table
+        chain.set_table_refresh(pg.TABLE_GRAPH_MEMCPY)
+        us_ind_graph_memcpy = timed(pg.GRAPH_INDIRECT)
+        chain.set_table_refresh(pg.TABLE_HOST)
+        us_ind_host_table = timed(pg.GRAPH_INDIRECT)
+        chain.set_table_refresh(pg.TABLE_KERNARG)
+        log(f"[bench] graph_indirect, pointers by a copy node inside the graph: {us_ind_graph_memcpy:.1f}; from a host-resident table: {us_ind_host_table:.1f} us/iteration")
         us_update = timed(pg.GRAPH_UPDATE)
         log(f"[bench] graph with host-side node updates: {us_update:.1f} us/iteration")
         chain.set_copy_refresh(pg.COPY_MEMCPY)
@@ -227,6 +234,7 @@ def main() -> int:
         "launches_per_s": {m: n_k / us[m] * 1e6 for m in us},
         "speedup_vs_eager": {m: us["eager"] / us[m] for m in us},
         "graph_indirect_memcpy_table_us": us_ind_memcpy,
+        "graph_indirect_copy_node_in_graph_us": us_ind_graph_memcpy, "graph_indirect_host_table_us": us_ind_host_table,
         "graph_host_node_update_us": us_update, "graph_copy_per_tensor_memcpy_us": us_copy_memcpy,
         "selection": {"cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()], "mode": sel.tolist()},
         "idle_gap_fraction": None,   # needs per-kernel durations: taken from the rocprofv3 kernel trace, reported with the profile summaries

@@ -100,9 +100,17 @@ typedef struct {
 /* How pg_replay_indirect moves the pointers host -> device (paper, Sec. 4 "Graph-Capture
  * Layer": pointer copies are host-to-device transfers, unlike the device-to-device data copies). */
 typedef enum {
-    PG_TABLE_KERNARG = 0,  /* a one-wave kernel whose argument block carries the pointers      */
-    PG_TABLE_MEMCPY = 1    /* hipMemcpyAsync from a ring of pinned staging slots               */
+    PG_TABLE_KERNARG = 0,      /* a one-wave kernel whose argument block carries the pointers          */
+    PG_TABLE_MEMCPY = 1,       /* hipMemcpyAsync from a ring of pinned staging slots                   */
+    PG_TABLE_GRAPH_MEMCPY = 2, /* the copy is the first node of the indirect graph itself: the host only
+                                  fills pinned staging and launches the graph                         */
+    PG_TABLE_HOST = 3          /* the table lives in pinned host memory: the host only writes it, the
+                                  kernels' dereference crosses the host link                          */
 } pg_table_refresh;
+/* The last two read host memory when the graph runs, not when the call returns, so they alternate
+ * between two instances (staging / table + graphs) and a call first waits, on the host, for the
+ * replay that last used its instance; their graphs are built by the first indirect replay after
+ * they are selected (which synchronises the stream and must not be captured). */
 
 /* How a copy-mode replay moves the data of the external inputs into the placeholders (Sec. 2.2:
  * the deployed systems copy parameter by parameter; Sec. 5, table of bytes copied). */

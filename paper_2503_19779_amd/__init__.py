@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     GRAPH_UPDATE,
     TABLE_KERNARG,
     TABLE_MEMCPY,
+    TABLE_GRAPH_MEMCPY,
+    TABLE_HOST,
     COPY_KERNEL,
     COPY_MEMCPY,
 )

@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 EAGER, GRAPH_COPY, GRAPH_INDIRECT, SELECTED, GRAPH_UPDATE = 0, 1, 2, 3, 4
-TABLE_KERNARG, TABLE_MEMCPY = 0, 1
+TABLE_KERNARG, TABLE_MEMCPY, TABLE_GRAPH_MEMCPY, TABLE_HOST = 0, 1, 2, 3
 COPY_KERNEL, COPY_MEMCPY = 0, 1
 
 _DT = {"f32": 0, "bf16": 1}

@@ -67,6 +67,14 @@ def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile
     chain.time_loop(pg.GRAPH_COPY, sets, warmup, stream)
     us["graph_copy_per_tensor_memcpy"] = chain.time_loop(pg.GRAPH_COPY, sets, iters, stream)
     chain.set_copy_refresh(pg.COPY_KERNEL)
+    # the other ways of getting the pointers to the kernels (the default is a writer kernel)
+    if chain.n_ext:
+        for name, how in (("graph_indirect_pinned_memcpy", pg.TABLE_MEMCPY), ("graph_indirect_copy_node_in_graph", pg.TABLE_GRAPH_MEMCPY),
+                          ("graph_indirect_host_table", pg.TABLE_HOST)):
+            chain.set_table_refresh(how)
+            chain.time_loop(pg.GRAPH_INDIRECT, sets, warmup, stream)
+            us[name] = chain.time_loop(pg.GRAPH_INDIRECT, sets, iters, stream)
+        chain.set_table_refresh(pg.TABLE_KERNARG)
     st = chain.stats()
     return chain, {"us_per_iteration": us, "capture_ms": cap_ms,
                    "cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()],

@@ -61,6 +61,7 @@ union ArgBlock {
 struct KernelRec {
     pgk::Launch direct, indirect;   // same shape, different kernel variant
     ArgBlock a_eager, a_copy, a_ind, a_upd;
+    ArgBlock a_host[2];             // external operands are slots of the two host-resident tables (PG_TABLE_HOST)
     int n_in = 0;
     int ind_mask = 0;               // operands that are external
     int ext_of[3] = {-1, -1, -1};
@@ -86,6 +87,21 @@ struct Segment {
     hipGraph_t g_upd = nullptr;
     hipGraphExec_t x_upd[2] = {nullptr, nullptr};
     std::vector<hipGraphNode_t> nodes;
+    // indirect graphs of the two table mechanisms that alternate between two instances:
+    // [0] PG_TABLE_GRAPH_MEMCPY, [1] PG_TABLE_HOST
+    hipGraph_t g_alt[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+    hipGraphExec_t x_alt[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+};
+
+// A table mechanism whose host-side buffer is read by the GPU when the graph runs, not when the call
+// returns: two instances alternate, and an instance is rewritten only after the replay that last
+// used it has finished (an event per instance).
+struct AltTable {
+    bool built = false;
+    void* host[2] = {nullptr, nullptr};          // pinned: staging of the in-graph copy, or the table itself
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    bool used[2] = {false, false};
+    unsigned long long cnt = 0;
 };
 
 }  // namespace
@@ -117,6 +133,7 @@ struct pg_chain {
     unsigned long long ring_cnt = 0;
     hipEvent_t ring_ev[2] = {nullptr, nullptr};
     bool ring_used[2] = {false, false};
+    AltTable alt[2];                    // [0] PG_TABLE_GRAPH_MEMCPY, [1] PG_TABLE_HOST
 };
 
 namespace {
@@ -442,8 +459,21 @@ void destroy_update_graphs(pg_chain* c) {
     c->upd_used[0] = c->upd_used[1] = false;
 }
 
+void destroy_alt_graphs(pg_chain* c) {
+    for (auto& s : c->seg)
+        for (int v = 0; v < 2; v++)
+            for (int i = 0; i < 2; i++) {
+                if (s.x_alt[v][i]) (void)hipGraphExecDestroy(s.x_alt[v][i]);
+                if (s.g_alt[v][i]) (void)hipGraphDestroy(s.g_alt[v][i]);
+                s.x_alt[v][i] = nullptr;
+                s.g_alt[v][i] = nullptr;
+            }
+    for (auto& a : c->alt) { a.built = false; a.used[0] = a.used[1] = false; }
+}
+
 void destroy_graphs(pg_chain* c) {
     destroy_update_graphs(c);
+    destroy_alt_graphs(c);
     for (auto& s : c->seg) {
         if (s.x_ind && s.x_ind != s.x_copy) (void)hipGraphExecDestroy(s.x_ind);
         if (s.g_ind && s.g_ind != s.g_copy) (void)hipGraphDestroy(s.g_ind);
@@ -521,12 +551,21 @@ pg_status run_update(pg_chain* c, const void* const* ext, hipStream_t s) {
     return PG_OK;
 }
 
-pg_status capture_segment(pg_chain* c, Segment& sg, bool indirect, hipStream_t s, hipGraph_t* g_out, hipGraphExec_t* x_out) {
+// What a captured graph's kernels read their external operands from.
+enum GraphKind { kGraphCopy = 0, kGraphTable = 1, kGraphTableMemcpyNode = 2, kGraphHostTable = 3 };
+
+pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStream_t s, hipGraph_t* g_out, hipGraphExec_t* x_out) {
     PG_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
     hipError_t le = hipSuccess;
+    if (kind == kGraphTableMemcpyNode)   // the graph's first node copies the pointers from its instance's pinned staging
+        le = hipMemcpyAsync(c->ws + c->table_off, c->alt[0].host[inst], c->ext.size() * 8, hipMemcpyHostToDevice, s);
     for (int i = sg.k0; i < sg.k1 && le == hipSuccess; i++) {
         KernelRec& r = c->rec[i];
-        le = indirect ? launch(r.indirect, &r.a_ind, s) : launch(r.direct, &r.a_copy, s);
+        switch (kind) {
+        case kGraphCopy: le = launch(r.direct, &r.a_copy, s); break;
+        case kGraphHostTable: le = launch(r.indirect, &r.a_host[inst], s); break;
+        default: le = launch(r.indirect, &r.a_ind, s); break;
+        }
     }
     hipGraph_t g = nullptr;
     hipError_t ee = hipStreamEndCapture(s, &g);   // always end the capture, even after a failed launch
@@ -541,7 +580,68 @@ pg_status capture_segment(pg_chain* c, Segment& sg, bool indirect, hipStream_t s
     return PG_OK;
 }
 
-pg_status run_segment(pg_chain* c, int si, int mode, const void* const* ext, hipStream_t s, bool* table_written) {
+// ---- the indirect refresh of one call, whichever table mechanism is selected ------------------------
+struct IndCtx { bool begun = false; int inst = 0; };
+
+pg_status build_alt(pg_chain* c, int v, hipStream_t s) {
+    AltTable& a = c->alt[v];
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    PG_HIP(hipStreamIsCapturing(s, &cs));
+    if (cs != hipStreamCaptureStatusNone) return fail(PG_EINVAL, "the first indirect replay with this table mechanism builds graphs and cannot run on a capturing stream");
+    const size_t bytes = std::max<size_t>(1, c->ext.size()) * 8;
+    for (int i = 0; i < 2; i++) {
+        if (!a.host[i]) PG_HIP(hipHostMalloc(&a.host[i], bytes, hipHostMallocDefault));
+        memset(a.host[i], 0, bytes);
+        if (!a.ev[i]) PG_HIP(hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming));
+    }
+    if (v == 1)     // kernels dereference slots of the host-resident table: pinned memory has one address on both sides
+        for (auto& r : c->rec)
+            for (int i = 0; i < 2; i++) {
+                r.a_host[i] = r.a_ind;
+                for (int j = 0; j < r.n_in; j++)
+                    if (r.ext_of[j] >= 0) r.a_host[i].ptr[1 + j] = static_cast<const char*>(a.host[i]) + 8 * (size_t)r.ext_of[j];
+            }
+    for (auto& sg : c->seg) {
+        if (!sg.has_ext) continue;    // such a segment replays its copy graph in every mode
+        for (int i = 0; i < 2; i++) {
+            pg_status st = capture_segment(c, sg, v == 0 ? kGraphTableMemcpyNode : kGraphHostTable, i, s, &sg.g_alt[v][i], &sg.x_alt[v][i]);
+            if (st) { destroy_alt_graphs(c); return st; }
+        }
+    }
+    PG_HIP(hipStreamSynchronize(s));
+    a.built = true;
+    return PG_OK;
+}
+
+pg_status ind_begin(pg_chain* c, const void* const* ext, hipStream_t s, IndCtx& x) {
+    if (x.begun) return PG_OK;
+    x.begun = true;
+    if (c->table_how == PG_TABLE_KERNARG || c->table_how == PG_TABLE_MEMCPY) return write_table(c, ext, s);
+    const int v = c->table_how - PG_TABLE_GRAPH_MEMCPY;
+    AltTable& a = c->alt[v];
+    if (!a.built) { pg_status st = build_alt(c, v, s); if (st) { x.begun = false; return st; } }
+    x.inst = (int)(a.cnt & 1);
+    if (a.used[x.inst]) PG_HIP(hipEventSynchronize(a.ev[x.inst]));   // the replay that last read this instance
+    memcpy(a.host[x.inst], ext, c->ext.size() * 8);
+    return PG_OK;
+}
+
+hipGraphExec_t ind_exec(pg_chain* c, Segment& sg, const IndCtx& x) {
+    if (!sg.has_ext) return sg.x_copy;
+    if (c->table_how == PG_TABLE_KERNARG || c->table_how == PG_TABLE_MEMCPY) return sg.x_ind;
+    return sg.x_alt[c->table_how - PG_TABLE_GRAPH_MEMCPY][x.inst];
+}
+
+pg_status ind_end(pg_chain* c, hipStream_t s, IndCtx& x) {
+    if (!x.begun || c->table_how == PG_TABLE_KERNARG || c->table_how == PG_TABLE_MEMCPY) return PG_OK;
+    AltTable& a = c->alt[c->table_how - PG_TABLE_GRAPH_MEMCPY];
+    PG_HIP(hipEventRecord(a.ev[x.inst], s));
+    a.used[x.inst] = true;
+    a.cnt++;
+    return PG_OK;
+}
+
+pg_status run_segment(pg_chain* c, int si, int mode, const void* const* ext, hipStream_t s, IndCtx* ind) {
     Segment& sg = c->seg[si];
     switch (mode) {
     case PG_EAGER: return run_eager_range(c, sg.k0, sg.k1, ext, s);
@@ -552,8 +652,9 @@ pg_status run_segment(pg_chain* c, int si, int mode, const void* const* ext, hip
     }
     case PG_GRAPH_INDIRECT: {
         if (!sg.has_ext) return fail(PG_EUNAVAIL, "segment %d reads no external operand: indirect mode does not exist for it", si);
-        if (!*table_written) { pg_status st = write_table(c, ext, s); if (st) return st; *table_written = true; }
-        PG_HIP(hipGraphLaunch(sg.x_ind, s));
+        pg_status st = ind_begin(c, ext, s, *ind);
+        if (st) return st;
+        PG_HIP(hipGraphLaunch(ind_exec(c, sg, *ind), s));
         return PG_OK;
     }
     default: return fail(PG_EINVAL, "bad mode %d for segment %d", mode, si);
@@ -665,10 +766,10 @@ pg_status pg_capture(pg_chain* c, void* hip_stream) {
         PG_HIP(hipEventCreateWithFlags(&c->ring_ev[1], hipEventDisableTiming));
     }
     for (auto& sg : c->seg) {
-        pg_status st = capture_segment(c, sg, false, s, &sg.g_copy, &sg.x_copy);
+        pg_status st = capture_segment(c, sg, kGraphCopy, 0, s, &sg.g_copy, &sg.x_copy);
         if (st) { destroy_graphs(c); return st; }
         if (sg.has_ext) {
-            st = capture_segment(c, sg, true, s, &sg.g_ind, &sg.x_ind);
+            st = capture_segment(c, sg, kGraphTable, 0, s, &sg.g_ind, &sg.x_ind);
             if (st) { destroy_graphs(c); return st; }
         } else {
             sg.g_ind = sg.g_copy;   // no external operand: the two graphs would be identical
@@ -702,7 +803,9 @@ pg_status pg_refresh_copy(pg_chain* c, const void* const* ext, void* hip_stream)
 pg_status pg_refresh_indirect(pg_chain* c, const void* const* ext, void* hip_stream) {
     pg_status st = check_call(c, ext, hip_stream, true);
     if (st) return st;
-    return write_table(c, ext, static_cast<hipStream_t>(hip_stream));
+    IndCtx x;
+    if ((st = ind_begin(c, ext, static_cast<hipStream_t>(hip_stream), x))) return st;
+    return ind_end(c, static_cast<hipStream_t>(hip_stream), x);
 }
 
 pg_status pg_replay_copy(pg_chain* c, const void* const* ext, void* hip_stream) {
@@ -718,9 +821,10 @@ pg_status pg_replay_indirect(pg_chain* c, const void* const* ext, void* hip_stre
     pg_status st = check_call(c, ext, hip_stream, true);
     if (st) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if ((st = write_table(c, ext, s))) return st;
-    for (auto& sg : c->seg) PG_HIP(hipGraphLaunch(sg.x_ind, s));
-    return PG_OK;
+    IndCtx x;
+    if ((st = ind_begin(c, ext, s, x))) return st;
+    for (auto& sg : c->seg) PG_HIP(hipGraphLaunch(ind_exec(c, sg, x), s));
+    return ind_end(c, s, x);
 }
 
 pg_status pg_replay_update(pg_chain* c, const void* const* ext, void* hip_stream) {
@@ -739,10 +843,10 @@ pg_status pg_run_selected(pg_chain* c, const uint8_t* mode, const void* const* e
     pg_status st = check_call(c, ext, hip_stream, true);
     if (st) return st;
     if (!mode) return fail(PG_EINVAL, "null mode array");
-    bool table_written = false;
+    IndCtx x;
     for (int si = 0; si < (int)c->seg.size(); si++)
-        if ((st = run_segment(c, si, mode[si], ext, static_cast<hipStream_t>(hip_stream), &table_written))) return st;
-    return PG_OK;
+        if ((st = run_segment(c, si, mode[si], ext, static_cast<hipStream_t>(hip_stream), &x))) return st;
+    return ind_end(c, static_cast<hipStream_t>(hip_stream), x);
 }
 
 pg_status pg_select(const double* cost, int32_t n_seg, uint8_t* mode_out) {
@@ -776,8 +880,9 @@ pg_status pg_profile(pg_chain* c, const void* const* ext, void* hip_stream, int3
             for (int it = -2; it < iters; it++) {   // two warm-ups
                 const double t0 = now_us();
                 for (int r = 0; r < inner; r++) {
-                    bool tw = false;
-                    if ((st = run_segment(c, si, m, ext, s, &tw))) return st;
+                    IndCtx x;
+                    if ((st = run_segment(c, si, m, ext, s, &x))) return st;
+                    if ((st = ind_end(c, s, x))) return st;
                 }
                 PG_HIP(hipStreamSynchronize(s));
                 if (it >= 0) samples[it] = (now_us() - t0) / inner;
@@ -921,7 +1026,7 @@ pg_status pg_chain_stats(const pg_chain* c, pg_stats* out) {
 }
 
 pg_status pg_set_table_refresh(pg_chain* c, int32_t how) {
-    if (!c || (how != PG_TABLE_KERNARG && how != PG_TABLE_MEMCPY)) return fail(PG_EINVAL, "bad table refresh kind");
+    if (!c || how < PG_TABLE_KERNARG || how > PG_TABLE_HOST) return fail(PG_EINVAL, "bad table refresh kind");
     c->table_how = how;
     return PG_OK;
 }
@@ -935,6 +1040,11 @@ pg_status pg_set_copy_refresh(pg_chain* c, int32_t how) {
 void pg_chain_destroy(pg_chain* c) {
     if (!c) return;
     destroy_graphs(c);
+    for (auto& a : c->alt)
+        for (int i = 0; i < 2; i++) {
+            if (a.ev[i]) (void)hipEventDestroy(a.ev[i]);
+            if (a.host[i]) (void)hipHostFree(a.host[i]);
+        }
     if (c->upd_ev[0]) (void)hipEventDestroy(c->upd_ev[0]);
     if (c->upd_ev[1]) (void)hipEventDestroy(c->upd_ev[1]);
     if (c->ring_ev[0]) (void)hipEventDestroy(c->ring_ev[0]);

@@ -100,9 +100,11 @@ def test_idempotence_and_interleaving():
     h.close()
 
 
-@pytest.mark.parametrize("how", [pg.TABLE_KERNARG, pg.TABLE_MEMCPY])
+@pytest.mark.parametrize("how", [pg.TABLE_KERNARG, pg.TABLE_MEMCPY, pg.TABLE_GRAPH_MEMCPY, pg.TABLE_HOST])
 def test_table_refresh_mechanisms(how):
-    """Both ways of moving the pointers host -> device; enough replays to wrap the staging ring."""
+    """Every way of getting the pointers to the kernels (writer kernel, memcpy from a pinned ring, a
+    copy node inside the graph, a host-resident table); enough replays to wrap the staging ring and to
+    reuse both instances of the alternating mechanisms many times."""
     h = Harness(elementwise_chain(n_kernels=9, numel=1024))
     h.chain.set_table_refresh(how)
     sets = [h.inputs(t) for t in range(3)]
@@ -197,3 +199,40 @@ def test_selected_is_as_fast_as_the_best_single_mode():
         say(f"{spec.name}: {us} selected {sel.tolist()}")
         assert us["selected"] <= 1.25 * min(us["eager"], us["copy"], us["indirect"]), us
         h.close()
+
+
+@pytest.mark.parametrize("how", [pg.TABLE_GRAPH_MEMCPY, pg.TABLE_HOST])
+def test_alternating_table_mechanisms_in_mixed_modes(how):
+    """Segments in different modes within one call, inputs at fresh addresses every iteration, under
+    the two table mechanisms that alternate instances; then back to the default mechanism."""
+    spec = tiny_mixed_chain("bf16", seed=11, segments=True)
+    h = Harness(spec)
+    h.chain.set_table_refresh(how)
+    for t in range(6):
+        x_np, x = h.inputs(t)
+        ref = h.run("eager", x)
+        want = h.oracle(x_np)
+        for modes in ([2, 2, 2], [1, 0, 2], [2, 1, 0], [0, 2, 1]):
+            h.scrub()
+            got = h.run("selected", x, modes=modes)
+            for a, b in zip(got, ref):
+                assert same_bits(a, b), (t, modes)
+        h.scrub()
+        got = h.run("indirect", x)
+        for a, b, w in zip(got, ref, want):
+            assert same_bits(a, b)
+            assert_close(a, w, "bf16", f"table mechanism {how} iteration {t}")
+    cost = h.chain.profile(h.inputs(7)[1], h.stream, iters=3, inner=2)
+    assert np.all(np.isfinite(cost)) and np.all(cost > 0)
+    h.chain.set_table_refresh(pg.TABLE_KERNARG)
+    x_np, x = h.inputs(9)
+    ref = h.run("eager", x)
+    h.scrub()
+    for a, b in zip(h.run("indirect", x), ref):
+        assert same_bits(a, b)
+    h.chain.capture(h.stream)            # a re-capture drops the alternating graphs; they are rebuilt on demand
+    h.chain.set_table_refresh(how)
+    h.scrub()
+    for a, b in zip(h.run("indirect", x), ref):
+        assert same_bits(a, b)
+    h.close()

@@ -232,6 +232,8 @@ def test_calls_out_of_order_or_with_bad_pointers():
         ch.capture(0)
     with pytest.raises(pg.PgError):
         ch.set_table_refresh(7)
+    for how in (pg.TABLE_KERNARG, pg.TABLE_MEMCPY, pg.TABLE_GRAPH_MEMCPY, pg.TABLE_HOST, pg.TABLE_KERNARG):
+        ch.set_table_refresh(how)
     with pytest.raises(pg.PgError):
         ch.set_copy_refresh(-1)
     ch.set_copy_refresh(pg.COPY_MEMCPY)
