@@ -622,7 +622,7 @@ pg_status ind_begin(pg_chain* c, const void* const* ext, hipStream_t s, IndCtx& 
     if (!a.built) { pg_status st = build_alt(c, v, s); if (st) { x.begun = false; return st; } }
     x.inst = (int)(a.cnt & 1);
     if (a.used[x.inst]) PG_HIP(hipEventSynchronize(a.ev[x.inst]));   // the replay that last read this instance
-    memcpy(a.host[x.inst], ext, c->ext.size() * 8);
+    if (!c->ext.empty()) memcpy(a.host[x.inst], ext, c->ext.size() * 8);
     return PG_OK;
 }
 

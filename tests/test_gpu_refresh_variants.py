@@ -166,3 +166,32 @@ def test_scalars_as_one_element_tensors(dtype):
         outs.append(ref)
     assert not same_bits(outs[0], outs[1])   # the scalars did change the result
     h.close()
+
+
+def test_chain_without_external_inputs_in_every_path():
+    """A chain that reads only weights: nothing to refresh, every replay path still runs it."""
+    n = 3000
+    ks = [KernelSpec("mul", "f32", 0, (Ref(WEIGHT, 0), Ref(WEIGHT, 1)), n, 0, m=n),
+          KernelSpec("gelu", "f32", 0, (Ref(INT, 0),), n, 0),
+          KernelSpec("add", "f32", 0, (Ref(INT, 0), Ref(WEIGHT, 1)), n, 1, m=n)]
+    spec = ChainSpec("no_ext", ks, [], [TensorSpec("f32", n)], [TensorSpec("f32", n), TensorSpec("f32", n)], [0], 5)
+    h = Harness(spec)
+    want = h.oracle([])[0]
+    ref = h.run("eager", [])[0]
+    assert_close(ref, want, "f32", "no external inputs")
+    for how in (pg.TABLE_KERNARG, pg.TABLE_MEMCPY, pg.TABLE_GRAPH_MEMCPY, pg.TABLE_HOST):
+        h.chain.set_table_refresh(how)
+        for mode in ("copy", "indirect"):
+            h.scrub()
+            assert same_bits(h.run(mode, [])[0], ref), (how, mode)
+    h.chain.set_copy_refresh(pg.COPY_MEMCPY)
+    h.scrub()
+    assert same_bits(h.run("copy", [])[0], ref)
+    h.scrub()
+    assert same_bits(run_update(h, [])[0], ref)
+    cost = h.chain.profile([], h.stream, iters=3, inner=2)
+    assert np.all(np.isnan(cost[:, 2])) and np.all(cost[:, :2] > 0)      # no indirect variant anywhere
+    assert pg.select(cost).max() <= 1
+    st = h.chain.stats()
+    assert st["copy_bytes_per_replay"] == 0 and st["table_bytes_per_replay"] == 0
+    h.close()
