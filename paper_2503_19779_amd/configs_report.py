@@ -2,8 +2,9 @@
 
     python -m paper_2503_19779_amd.configs_report --config 0 1 3 4 5
 
-(config 0 is the launch floor: 512 dependent kernels on 64 elements each; config 6 sweeps the
-batch-1 GEMV over matrix sizes.)
+(config 0 is the launch floor: 512 dependent kernels on 64 elements each; 6 sweeps the batch-1
+GEMV over matrix sizes; 7 is the decode chain read literally; 8 the GEMV at every batch size;
+9 compares cost tables predicted from a few measured constants with the profiled ones.)
 
 Per chain: capture, slow-path profile -> cost table -> selection, then microseconds per iteration
 for eager, graph-copy, graph-indirect and the selected mixture (back-to-back iterations on one
@@ -44,6 +45,42 @@ def chain_bytes(spec) -> int:
         else:
             total += (2 * k.n + 2 * k.channels) * e
     return total
+
+
+def kernel_bytes(k) -> int:
+    e = {"f32": 4, "bf16": 2}[k.dtype]
+    if k.op in ("add", "mul"):
+        return (2 * k.n + min(k.m or k.n, k.n)) * e
+    if k.op == "gelu":
+        return 2 * k.n * e
+    if k.op == "rmsnorm":
+        return (2 * k.rows * k.cols + k.cols) * e
+    if k.op == "gemv":
+        return (k.n * k.cols + k.rows * k.cols + k.rows * k.n) * e
+    return (2 * k.n + 2 * k.channels) * e
+
+
+def model_cost(spec, c) -> np.ndarray:
+    """The cost table predicted from a handful of measured constants instead of profiled per chain:
+    launch cost saved against copy cost added (Sec. 3 "Selective CUDA Graphs" argues with exactly
+    these terms).  Per kernel the GPU needs a dispatch slot plus its memory time; eager costs the slower of the host's launches and the GPU's slots; a graph
+    costs one graph launch plus its nodes, plus either the copy kernel (a node and 2 x the bytes) or
+    the table writer (a node) and one dereference per external-reading kernel."""
+    n_seg = spec.kernels[-1].segment + 1
+    out = np.full((n_seg, 3), np.nan)
+    for s in range(n_seg):
+        ks = [k for k in spec.kernels if k.segment == s]
+        # memory time of a kernel on top of its slot; one that streams from HBM also waits for its first byte
+        extra = [kernel_bytes(k) / c["kernel_GBps"] / 1e3 + (c["first_byte_us"] if kernel_bytes(k) >= (1 << 20) else 0.0) for k in ks]
+        ext = sorted({r.index for k in ks for r in k.ins if r.kind == "ext"})
+        readers = sum(1 for k in ks if any(r.kind == "ext" for r in k.ins))
+        copy_bytes = sum(spec.ext[i].nbytes for i in ext)
+        out[s, 0] = max(len(ks) * c["eager_launch_us"], len(ks) * c["stream_node_us"] + sum(extra))
+        graph = c["graph_launch_us"] + len(ks) * c["graph_node_us"] + sum(extra)
+        out[s, 1] = graph + ((c["graph_node_us"] + 2 * copy_bytes / c["copy_GBps"] / 1e3) if ext else 0.0)
+        if ext:
+            out[s, 2] = graph + c["graph_node_us"] + readers * c["deref_us"]
+    return out
 
 
 def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile_iters=10):
@@ -129,6 +166,64 @@ def main() -> int:
                 log(f"[configs] GEMV {H} x {H}: {us:.2f} us per launch, {b / us / 1e3:.0f} GB/s")
                 del mats, vec
             print(json.dumps({"config": 6, "workload": "batch-1 bf16 GEMV size sweep, 24 launches per graph", "gemv": rows_out}), flush=True)
+            continue
+        if cfg == 9:
+            # Predicted against profiled cost tables.  The constants come from three small measurements
+            # (a do-nothing chain, a one-kernel chain, the large-tensor chain), not from the chains judged.
+            from pg_workloads import decode_chain
+            floor = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
+            ch = pg.Chain(floor, [])
+            ch.capture(stream)
+            fx = host_sets(floor, 3)()
+            t = {}
+            for name, mode in (("eager", pg.EAGER), ("graph", pg.GRAPH_INDIRECT)):
+                ch.time_loop(mode, fx, 10, stream)
+                t[name] = ch.time_loop(mode, fx, 100, stream)
+            ch.close()
+            one = elementwise_chain(n_kernels=1, numel=64, dtype="bf16")
+            ch = pg.Chain(one, [])
+            ch.capture(stream)
+            ox = host_sets(one, 3)()
+            one_cost = ch.profile(ox[0], stream, iters=21, inner=1)     # launch + run + synchronise, once
+            ch.close()
+            big = large_tensor_chain()
+            wb = [to_device(a) for a in make_weights(big)]
+            ch = pg.Chain(big, wb)
+            bx = device_sets(big, 1)()[0]
+            d = ch.time_kernels(bx, stream)
+            d = ch.time_kernels(bx, stream)
+            ch.close()
+            stress = refresh_stress_chain()
+            ws = [to_device(a) for a in make_weights(stress)]
+            ch = pg.Chain(stress, ws)
+            ch.capture(stream)
+            sx = device_sets(stress, 2)()
+            cu = np.array([ch.time_refresh_copy(sx[i % 2], stream) for i in range(13)][3:])
+            ch.close()
+            del sx, ws
+            node = t["graph"] / 512
+            consts = {"eager_launch_us": t["eager"] / 512, "graph_node_us": node, "stream_node_us": node,
+                      "graph_launch_us": max(0.0, float(one_cost[0, 2] - one_cost[0, 0])),
+                      "first_byte_us": 0.4, "kernel_GBps": 2 * big.ext[0].nbytes / float(np.median(d)) / 1e3,
+                      "copy_GBps": 2 * stress.ext_bytes() / float(cu.mean()) / 1e3, "deref_us": 0.08}
+            log(f"[configs] model constants: {consts}")
+            rows_out = []
+            for name, spec, mk in (("config 1", elementwise_chain(), "host"), ("config 2", decode_chain(), "dev"),
+                                   ("config 3", stress, "dev"), ("config 4", big, "dev"), ("config 5, B=128", decode_chain(batch=128), "dev")):
+                w = [to_device(a) for a in make_weights(spec)]
+                ch = pg.Chain(spec, w)
+                ch.capture(stream)
+                x = (host_sets(spec, 1) if mk == "host" else device_sets(spec, 1))()[0]
+                prof = ch.profile(x, stream, iters=9, inner=2)
+                ch.close()
+                pred = model_cost(spec, consts)
+                sel_p, sel_m = pg.select(prof), pg.select(pred)
+                rows_out.append({"chain": name, "profiled_us": [[None if not np.isfinite(v) else round(float(v), 1) for v in r] for r in prof.tolist()],
+                                 "model_us": [[None if not np.isfinite(v) else round(float(v), 1) for v in r] for r in pred.tolist()],
+                                 "selected_from_profile": sel_p.tolist(), "selected_from_model": sel_m.tolist()})
+                log(f"[configs] {name}: profiled {rows_out[-1]['profiled_us']} -> {sel_p.tolist()}; model {rows_out[-1]['model_us']} -> {sel_m.tolist()}")
+                del w, x
+            print(json.dumps({"config": 9, "workload": "cost tables predicted from measured constants against profiled ones", "constants": consts, "chains": rows_out}), flush=True)
             continue
         if cfg == 8:
             # The batched GEMV alone at every bucket size: graphs of the decode chain's 120 launches over
