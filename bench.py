@@ -143,6 +143,20 @@ def main() -> int:
                 # HBM bytes per launch from the hardware-counter runs (FETCH_SIZE x 1.9996 + WRITE_SIZE x 1.0000,
                 # factors from a plain 256 MiB copy in the same run); the summary sits beside the other profiles
                 "traffic": 8.471e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
+    # The dispatch floor of this machine: the time per node of a graph of 512 dependent kernels that do next
+    # to nothing (64 elements each).  What the GEMV adds to it is its own memory time.
+    from pg_workloads import elementwise_chain
+    fspec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
+    fchain = pg.Chain(fspec, [], dev)
+    fchain.capture(stream)
+    fx = [[to_device(x, dev) for x in make_inputs(fspec, t)] for t in range(2)]
+    fchain.time_loop(pg.GRAPH_INDIRECT, fx, 10, stream)
+    floor_us = fchain.time_loop(pg.GRAPH_INDIRECT, fx, 50, stream) / len(fspec.kernels)
+    fchain.close()
+    roofline["dispatch_floor_us_per_node"] = floor_us
+    roofline["achieved_above_floor"] = gemv_bytes / max(gemv_us - floor_us, 1e-3) / 1e3
+    roofline["frac_above_floor"] = roofline["achieved_above_floor"] / HBM_PEAK
+    log(f"[bench] dispatch floor {floor_us:.2f} us per node; the GEMV's bytes over the time it adds to the floor: {roofline['achieved_above_floor']:.0f} GB/s")
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
 
