@@ -36,7 +36,9 @@ def main() -> int:
     ap.add_argument("--no-copy-bench", action="store_true", help="skip the copy-kernel bandwidth leg (config 3 sizes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-refresh-baselines", action="store_true",
-                    help="skip the refresh baselines (host-side node updates, per-tensor memcpy, the two alternating table mechanisms); the profiler runs use this")
+                    help="skip the legs added beside the three modes (host-side node updates, per-tensor memcpy, the two alternating table "
+                         "mechanisms, the dispatch-floor chain); the rocprofv3 runs use this: counter-collection runs that included them "
+                         "did not complete (one went silent, one ended in a segmentation fault inside a profiler thread)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
     args = ap.parse_args()
@@ -145,18 +147,20 @@ def main() -> int:
                 "traffic": 8.471e6, "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/gemv_and_copy_kernel_hbm_traffic.md"}
     # The dispatch floor of this machine: the time per node of a graph of 512 dependent kernels that do next
     # to nothing (64 elements each).  What the GEMV adds to it is its own memory time.
-    from pg_workloads import elementwise_chain
-    fspec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
-    fchain = pg.Chain(fspec, [], dev)
-    fchain.capture(stream)
-    fx = [[to_device(x, dev) for x in make_inputs(fspec, t)] for t in range(2)]
-    fchain.time_loop(pg.GRAPH_INDIRECT, fx, 10, stream)
-    floor_us = fchain.time_loop(pg.GRAPH_INDIRECT, fx, 50, stream) / len(fspec.kernels)
-    fchain.close()
-    roofline["dispatch_floor_us_per_node"] = floor_us
-    roofline["achieved_above_floor"] = gemv_bytes / max(gemv_us - floor_us, 1e-3) / 1e3
-    roofline["frac_above_floor"] = roofline["achieved_above_floor"] / HBM_PEAK
-    log(f"[bench] dispatch floor {floor_us:.2f} us per node; the GEMV's bytes over the time it adds to the floor: {roofline['achieved_above_floor']:.0f} GB/s")
+    # (Left out of the profiler runs together with the refresh baselines: see the flag's help text.)
+    if not args.no_refresh_baselines:
+        from pg_workloads import elementwise_chain
+        fspec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
+        fchain = pg.Chain(fspec, [], dev)
+        fchain.capture(stream)
+        fx = [[to_device(x, dev) for x in make_inputs(fspec, t)] for t in range(2)]
+        fchain.time_loop(pg.GRAPH_INDIRECT, fx, 10, stream)
+        floor_us = fchain.time_loop(pg.GRAPH_INDIRECT, fx, 50, stream) / len(fspec.kernels)
+        fchain.close()
+        roofline["dispatch_floor_us_per_node"] = floor_us
+        roofline["achieved_above_floor"] = gemv_bytes / max(gemv_us - floor_us, 1e-3) / 1e3
+        roofline["frac_above_floor"] = roofline["achieved_above_floor"] / HBM_PEAK
+        log(f"[bench] dispatch floor {floor_us:.2f} us per node; the GEMV's bytes over the time it adds to the floor: {roofline['achieved_above_floor']:.0f} GB/s")
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
 
