@@ -37,7 +37,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-refresh-baselines", action="store_true",
                     help="skip the legs added beside the three modes (host-side node updates, per-tensor memcpy, the two alternating table "
-                         "mechanisms, the dispatch-floor chain); the rocprofv3 runs use this: counter-collection runs that included them "
+                         "mechanisms, the dispatch-floor chain, the event-timed medians); the rocprofv3 runs use this: counter-collection runs that included them "
                          "did not complete (one went silent, one ended in a segmentation fault inside a profiler thread)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
@@ -85,11 +85,15 @@ def main() -> int:
         torch.cuda.synchronize()
         return us
 
-    us = {}
+    us, us_median, us_p90 = {}, {}, {}
     for name, mode, modes in (("eager", pg.EAGER, None), ("graph_copy", pg.GRAPH_COPY, None),
                               ("graph_indirect", pg.GRAPH_INDIRECT, None), ("selected", pg.SELECTED, sel)):
         us[name] = timed(mode, modes)
         log(f"[bench] {name}: {us[name]:.1f} us/iteration")
+        if not args.no_refresh_baselines:
+            each = chain.time_loop_each(mode, x_dev, min(K, 100), stream, modes)     # per-iteration times, from events on the stream
+            us_median[name], us_p90[name] = float(np.median(each)), float(np.quantile(each, 0.9))
+            log(f"[bench] {name}: median {us_median[name]:.1f}, p90 {us_p90[name]:.1f} us over {len(each)} event-timed iterations")
     chain.set_table_refresh(pg.TABLE_MEMCPY)
     us_ind_memcpy = timed(pg.GRAPH_INDIRECT)
     chain.set_table_refresh(pg.TABLE_KERNARG)
@@ -248,7 +252,7 @@ def main() -> int:
         "config": {"workload": "decode-step chain, batch 1: 24 layers x 5 x (RMSNorm 2048 + bf16 GEMV 2048x2048 + GELU + residual add) + 31 input adds = 511 kernels/iteration, 32 fresh bf16[2048] inputs/iteration, weights ~N(0,0.02^2)",
                    "kernels_per_iteration": n_k, "external_inputs": len(spec.ext), "input_sets": n_sets,
                    "step": "one iteration in each of: eager, graph-copy, graph-indirect, selected"},
-        "us_per_iteration": us,
+        "us_per_iteration": us, "us_per_iteration_median": us_median, "us_per_iteration_p90": us_p90,
         "launches_per_s": {m: n_k / us[m] * 1e6 for m in us},
         "speedup_vs_eager": {m: us["eager"] / us[m] for m in us},
         "graph_indirect_memcpy_table_us": us_ind_memcpy,

@@ -211,6 +211,13 @@ pg_status pg_time_loop(pg_chain *chain, int32_t mode, const uint8_t *mode_per_se
                        const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
                        double *us_per_iter_out);
 
+/* The same loop with a HIP event after every iteration: us_each_out [host] receives `iters`
+ * completion-to-completion times in microseconds (for medians and spreads; the events add a marker
+ * per iteration to the stream, so their mean is slightly above pg_time_loop's). */
+pg_status pg_time_loop_each(pg_chain *chain, int32_t mode, const uint8_t *mode_per_segment,
+                            const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
+                            float *us_each_out);
+
 /* GPU execution time of each kernel: launches kernels [k_begin, k_end) eagerly (as pg_eager_range
  * does), each with a pair of events that take the kernel's own start and end timestamps,
  * synchronises the stream, and writes k_end - k_begin durations in microseconds to dur_us_out

@@ -77,6 +77,7 @@ def lib():
         L.pg_profile.argtypes = [vp, PP, vp, i32, i32, C.POINTER(C.c_double)]
         L.pg_run_selected.argtypes = [vp, C.POINTER(C.c_uint8), PP, vp]
         L.pg_time_loop.argtypes = [vp, i32, C.POINTER(C.c_uint8), PP, i32, i32, vp, C.POINTER(C.c_double)]
+        L.pg_time_loop_each.argtypes = [vp, i32, C.POINTER(C.c_uint8), PP, i32, i32, vp, C.POINTER(C.c_float)]
         L.pg_chain_int_buffer.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.pg_chain_placeholder.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.pg_chain_pointer_table.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_size_t)]
@@ -278,6 +279,23 @@ class Chain:
         us = C.c_double(0)
         _check(lib().pg_time_loop(self._h, mode, mp, flat, n_sets, iters, self._s(stream), C.byref(us)))
         return us.value
+
+    def time_loop_each(self, mode: int, ext_sets: Sequence[Sequence], iters: int, stream, modes=None) -> np.ndarray:
+        """Completion-to-completion microseconds of each of `iters` back-to-back iterations of one mode."""
+        n_sets = len(ext_sets)
+        flat = (C.c_void_p * max(1, n_sets * self.n_ext))()
+        for s, ext in enumerate(ext_sets):
+            if len(ext) != self.n_ext:
+                raise ValueError("wrong number of external tensors in a set")
+            for i, it in enumerate(ext):
+                flat[s * self.n_ext + i] = it if isinstance(it, int) else it.data_ptr()
+        mp = None
+        if modes is not None:
+            modes = np.ascontiguousarray(modes, dtype=np.uint8)
+            mp = modes.ctypes.data_as(C.POINTER(C.c_uint8))
+        out = np.zeros(iters, np.float32)
+        _check(lib().pg_time_loop_each(self._h, mode, mp, flat, n_sets, iters, self._s(stream), out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
 
     def time_kernels(self, ext, stream, k_begin: int = 0, k_end: Optional[int] = None) -> np.ndarray:
         """GPU execution time (microseconds) of each kernel in [k_begin, k_end), launched eagerly."""

@@ -922,6 +922,51 @@ pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segmen
     return PG_OK;
 }
 
+// The same loop with an event after every iteration: the time between consecutive events is one
+// iteration's completion-to-completion time on the GPU.  The events add a marker per iteration to the
+// stream, so the mean of these is slightly above pg_time_loop's; they are for the distribution.
+pg_status pg_time_loop_each(pg_chain* c, int32_t mode, const uint8_t* mode_per_segment, const void* const* ext_sets, int32_t n_sets,
+                            int32_t iters, void* hip_stream, float* us_each_out) {
+    if (!c || !us_each_out || n_sets <= 0 || iters <= 0) return fail(PG_EINVAL, "bad arguments");
+    const int n_ext = (int)c->ext.size();
+    pg_status st;
+    for (int i = 0; i < n_sets; i++)
+        if ((st = check_call(c, ext_sets + (size_t)i * n_ext, hip_stream, mode != PG_EAGER))) return st;
+    if (mode == 3 && !mode_per_segment) return fail(PG_EINVAL, "null mode array");
+    if (mode < 0 || mode > 4) return fail(PG_EINVAL, "bad mode");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<hipEvent_t> ev(iters + 1, nullptr);
+    auto cleanup = [&]() { for (auto e : ev) if (e) (void)hipEventDestroy(e); };
+    for (auto& e : ev) {
+        hipError_t he = hipEventCreate(&e);
+        if (he != hipSuccess) { cleanup(); g_hip_err = (int)he; return fail(PG_EHIP, "hipEventCreate failed: %s", hipGetErrorString(he)); }
+    }
+    hipError_t he = hipStreamSynchronize(s);
+    if (he == hipSuccess) he = hipEventRecord(ev[0], s);
+    st = PG_OK;
+    for (int it = 0; it < iters && he == hipSuccess && st == PG_OK; it++) {
+        const void* const* ext = ext_sets + (size_t)(it % n_sets) * n_ext;
+        switch (mode) {
+        case PG_EAGER: st = run_eager_range(c, 0, (int)c->k.size(), ext, s); break;
+        case PG_GRAPH_COPY: st = pg_replay_copy(c, ext, hip_stream); break;
+        case PG_GRAPH_INDIRECT: st = pg_replay_indirect(c, ext, hip_stream); break;
+        case 4: st = pg_replay_update(c, ext, hip_stream); break;
+        default: st = pg_run_selected(c, mode_per_segment, ext, hip_stream); break;
+        }
+        if (st == PG_OK) he = hipEventRecord(ev[it + 1], s);
+    }
+    if (he == hipSuccess) he = hipStreamSynchronize(s);     // also after a failed iteration: nothing stays pending on the events
+    for (int it = 0; it < iters && he == hipSuccess && st == PG_OK; it++) {
+        float ms = 0.f;
+        he = hipEventElapsedTime(&ms, ev[it], ev[it + 1]);
+        us_each_out[it] = ms * 1e3f;
+    }
+    cleanup();
+    if (st) return st;
+    if (he != hipSuccess) { g_hip_err = (int)he; return fail(PG_EHIP, "timed loop failed: %s", hipGetErrorString(he)); }
+    return PG_OK;
+}
+
 // Launch with start/stop events that take the kernel's own dispatch timestamps.
 static pg_status launch_timed(const void* fn, dim3 grid, dim3 block, void* argblock, hipStream_t s,
                               std::vector<hipEvent_t>& evs) {

@@ -236,3 +236,20 @@ def test_alternating_table_mechanisms_in_mixed_modes(how):
     for a, b in zip(h.run("indirect", x), ref):
         assert same_bits(a, b)
     h.close()
+
+
+def test_event_timed_loop_agrees_with_the_host_timed_one():
+    """Per-iteration times from events on the stream: positive, as many as asked for, and their mean
+    close to the host-clock mean of the same loop."""
+    h = Harness(elementwise_chain())
+    sets = [h.inputs(t)[1] for t in range(3)]
+    h._keep = sets
+    for mode in (pg.EAGER, pg.GRAPH_COPY, pg.GRAPH_INDIRECT):
+        h.chain.time_loop(mode, sets, 10, h.stream)
+        mean = h.chain.time_loop(mode, sets, 50, h.stream)
+        each = h.chain.time_loop_each(mode, sets, 50, h.stream)
+        assert each.shape == (50,) and np.all(each > 0)
+        assert 0.5 * mean < float(np.median(each)) < 2.0 * mean, (mode, mean, float(np.median(each)))
+    x_np, x = h.inputs(5)
+    assert_close(h.run("indirect", x)[0], h.oracle(x_np)[0], "f32", "after the timed loops")
+    h.close()
