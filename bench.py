@@ -230,6 +230,16 @@ def main() -> int:
         cpu_us = (time.time() - t0) / n_done * 1e6
         cpu = {"value": cpu_us, "unit": "us/iteration", "cores": oracle.max_threads(), "kind": "oracle",
                "sample": f"{n_done} whole iterations of the same 511-kernel chain and inputs ({time.time() - t0:.1f} s of wall time)"}
+        # the same oracle on one thread (two iterations): how much of the figure above is the core count
+        n_all = oracle.max_threads()
+        try:
+            oracle.set_threads(1)
+            t1 = time.time()
+            for i in range(2):
+                oracle.run_chain(spec, w_np, x_np[i % n_sets])
+            cpu["value_on_1_thread"] = (time.time() - t1) / 2 * 1e6
+        finally:
+            oracle.set_threads(n_all)
         # the sample doubles as a live parity check of the timed configuration
         chain.replay_indirect(x_dev[(n_done - 1) % n_sets], stream)
         stream.synchronize()
