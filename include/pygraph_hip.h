@@ -231,6 +231,9 @@ pg_status pg_time_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs,
 
 /* Accessors.  Host only. */
 pg_status pg_chain_int_buffer(const pg_chain *chain, int32_t int_index, void **dev_ptr_out, size_t *bytes_out);
+/* The same under the name a caller looks for when it wants a result: a chain's outputs are the
+ * internal buffers it designates. */
+pg_status pg_chain_output(const pg_chain *chain, int32_t int_index, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_placeholder(const pg_chain *chain, int32_t ext_index, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_pointer_table(const pg_chain *chain, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);

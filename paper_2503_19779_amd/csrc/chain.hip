@@ -1041,6 +1041,8 @@ pg_status pg_chain_int_buffer(const pg_chain* c, int32_t i, void** p, size_t* by
     return PG_OK;
 }
 
+pg_status pg_chain_output(const pg_chain* c, int32_t i, void** p, size_t* bytes) { return pg_chain_int_buffer(c, i, p, bytes); }
+
 pg_status pg_chain_placeholder(const pg_chain* c, int32_t i, void** p, size_t* bytes) {
     if (!c || i < 0 || i >= (int)c->ext.size()) return fail(PG_EINVAL, "bad external index");
     if (p) *p = c->ws + c->ph_off[i];
