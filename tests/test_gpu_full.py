@@ -201,3 +201,90 @@ def test_config5_buckets():
         assert same_bits(got, ref), (it, b)
     for h in hs:
         h.close()
+
+
+def _sample_indices(n, rng, k=200000):
+    head = np.arange(0, 5000, dtype=np.int64)
+    tail = np.arange(n - 5000, n, dtype=np.int64)
+    return np.unique(np.concatenate([head, tail, rng.integers(0, n, k, dtype=np.int64)]))
+
+
+def test_elementwise_beyond_2_31_elements():
+    """The 64-bit-index forms: add with a broadcast operand, then GELU in place, on 2^31 + 4099 bf16
+    elements (4.3 GB per tensor).  All modes agree bit for bit on the whole output; the oracle checks
+    a sample of it (first and last 5000 elements and 200 000 random ones)."""
+    from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, EXT, INT, WEIGHT, f32_to_bf16_bits
+    n, m = (1 << 31) + 4099, 4096
+    rng = np.random.Generator(np.random.PCG64(77))
+    b_np = f32_to_bf16_bits(rng.standard_normal(m).astype(np.float32))
+    spec = ChainSpec("big_ew", [KernelSpec("add", "bf16", 0, (Ref(EXT, 0), Ref(WEIGHT, 0)), n, 0, m=m),
+                                KernelSpec("gelu", "bf16", 0, (Ref(INT, 0),), n, 0)],
+                     [TensorSpec("bf16", n)], [TensorSpec("bf16", n)], [TensorSpec("bf16", m)], [0], 77)
+    say(f"big elementwise: n = {n}, workspace {2 * n * 2 / 1e9:.1f} GB")
+    h = Harness(spec, weights_np=[b_np])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    a = torch.empty(n, device="cuda", dtype=torch.bfloat16).normal_(0.0, 1.5, generator=g)
+    out = h.chain.int_buffer(0)
+    ref = None
+    for mode in ("eager", "copy", "indirect"):
+        out.fill_(float("nan"))
+        h.chain.placeholder(0).fill_(float("nan"))
+        torch.cuda.synchronize()
+        {"eager": h.chain.eager, "copy": h.chain.replay_copy, "indirect": h.chain.replay_indirect}[mode]([a], h.stream)
+        h.stream.synchronize()
+        if ref is None:
+            ref = out.clone()
+        else:
+            assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), mode
+        say(f"big elementwise: {mode} done")
+    idx = _sample_indices(n, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    a_s = to_numpy(a[idx_dev])
+    got = to_numpy(ref[idx_dev])
+    t = oracle.run_op("add", "bf16", [a_s, b_np[idx % m]], len(idx))
+    want = oracle.run_op("gelu", "bf16", [t], len(idx))
+    assert_close(got, want, "bf16", "2^31+ elements, sampled", rtol=2.0 ** -7)
+    assert not np.isnan(as_f64(got)).any()
+    h.close()
+
+
+def test_scale_bias_relu_beyond_2_31_elements():
+    """The 64-bit-index form of the per-channel kernel: fp32 [N, 3, 1024], 2^31 + 3072 elements."""
+    from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, EXT, INT, WEIGHT
+    C_, inner = 3, 1024
+    N = ((1 << 31) // (C_ * inner)) + 1
+    n = N * C_ * inner
+    assert n >= (1 << 31)
+    rng = np.random.Generator(np.random.PCG64(78))
+    s_np = (1.0 + 0.1 * rng.standard_normal(C_)).astype(np.float32)
+    bias_np = (0.1 * rng.standard_normal(C_)).astype(np.float32)
+    spec = ChainSpec("big_sbr", [KernelSpec("scale_bias_relu", "f32", 0, (Ref(EXT, 0), Ref(WEIGHT, 0), Ref(WEIGHT, 1)), n, 0, inner=inner, channels=C_)],
+                     [TensorSpec("f32", n)], [TensorSpec("f32", n)], [TensorSpec("f32", C_), TensorSpec("f32", C_)], [0], 78)
+    say(f"big scale+bias+relu: n = {n}, workspace {2 * n * 4 / 1e9:.1f} GB")
+    h = Harness(spec, weights_np=[s_np, bias_np])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(78)
+    x = torch.empty(n, device="cuda", dtype=torch.float32).normal_(0.0, 1.0, generator=g)
+    out = h.chain.int_buffer(0)
+    ref = None
+    for mode in ("eager", "copy", "indirect"):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        {"eager": h.chain.eager, "copy": h.chain.replay_copy, "indirect": h.chain.replay_indirect}[mode]([x], h.stream)
+        h.stream.synchronize()
+        if ref is None:
+            ref = out.clone()
+        else:
+            assert torch.equal(out.view(torch.int32), ref.view(torch.int32)), mode
+    idx = _sample_indices(n, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    xs, got = to_numpy(x[idx_dev]), to_numpy(ref[idx_dev])
+    ch = (idx // inner) % C_
+    want = np.empty(len(idx), np.float32)
+    for c in range(C_):          # one sample-sized oracle call per channel
+        sel = ch == c
+        k = int(sel.sum())
+        want[sel] = oracle.run_op("scale_bias_relu", "f32", [np.ascontiguousarray(xs[sel]), s_np[c:c + 1], bias_np[c:c + 1]], k, inner=k, channels=1)
+    assert_close(got, want, "f32", "2^31+ elements, sampled")
+    h.close()
