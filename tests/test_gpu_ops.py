@@ -47,7 +47,8 @@ def run_single(spec, ext_np, w_np, offsets=None, what=""):
 @pytest.mark.parametrize("op", ["add", "mul", "gelu"])
 @pytest.mark.parametrize("n,m,offs", [(1, 0, (0, 0)), (7, 0, (0, 0)), (4096, 0, (0, 0)), (4099, 0, (0, 0)),
                                        (300001, 0, (0, 0)), (9000, 8, (0, 0)), (9001, 24, (0, 0)), (5000, 7, (0, 0)),
-                                       (4099, 0, (4, 0)), (4100, 0, (0, 8)), (70000, 512, (0, 0))])
+                                       (4099, 0, (4, 0)), (4100, 0, (0, 8)), (70000, 512, (0, 0)),
+                                       (2500003, 0, (0, 0)), (2500003, 4096, (4, 0))])      # beyond 4 MB: four vectors per lane
 def test_elementwise(op, dtype, n, m, offs):
     rng = np.random.Generator(np.random.PCG64(100 + n))
     say(f"elementwise {op} {dtype} n={n} m={m} offs={offs}")
