@@ -16,6 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pg_oracle.c")
 _HDR = os.path.join(_HERE, "pg_oracle.h")
 _SO = os.path.join(_HERE, "libpg_oracle.so")
+# The mutation test points this at a deliberately broken build to show that the pins notice.
+_SO_OVERRIDE = os.environ.get("PG_ORACLE_SO_OVERRIDE")
 
 _DT = {"f32": 0, "bf16": 1}
 _OP = {"add": 0, "mul": 1, "gelu": 2, "rmsnorm": 3, "gemv": 4, "scale_bias_relu": 5}
@@ -46,8 +48,11 @@ def build(force: bool = True) -> str:
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
-        L = C.CDLL(_SO)
+        if _SO_OVERRIDE:
+            L = C.CDLL(_SO_OVERRIDE)
+        else:
+            build(force=False)
+            L = C.CDLL(_SO)
         L.orc_bf16_from_f64.restype = C.c_uint16
         L.orc_bf16_from_f64.argtypes = [C.c_double]
         L.orc_bf16_to_f64.restype = C.c_double

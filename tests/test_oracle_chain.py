@@ -69,6 +69,24 @@ def test_truncation_and_resumption():
     for a, b in zip(full, rest):
         assert np.array_equal(a, b, equal_nan=True)
     assert not np.array_equal(part[0], full[0])
+    # a resumed run executes kernels [k_begin, k_end) and nothing before them: kernel 5 reads
+    # whatever the caller left in buffer 0, here a constant no earlier kernel would produce
+    ints = [p.copy() for p in oracle.run_chain(chain, w, x, 0, 5)]
+    ints[0][:] = 3.0
+    got = oracle.run_chain(chain, w, x, 5, 6, ints=ints)
+    assert np.array_equal(got[0], np.full(8, 3.0, np.float32))
+    assert np.array_equal(got[1], oracle.run_op("scale_bias_relu", "f32", [got[0], w[2], w[3]], 8, inner=4, channels=2))
+
+
+def test_a_kernel_the_oracle_rejects_stops_the_chain_and_is_named():
+    import dataclasses
+    chain = tiny_mixed_chain("f32", seed=9)
+    w, x = make_weights(chain), make_inputs(chain, 0)
+    ks = list(chain.kernels)
+    ks[5] = dataclasses.replace(ks[5], inner=3)          # 8 elements are not a whole number of [2, 3] planes
+    bad = dataclasses.replace(chain, kernels=ks)
+    with pytest.raises(ValueError, match="kernel 5"):
+        oracle.run_chain(bad, w, x)
 
 
 def test_no_state_survives_an_iteration():

@@ -191,6 +191,20 @@ def test_gemv_integer_values_are_exact(dtype):
         assert np.array_equal(gotf, want.reshape(-1))
 
 
+def test_bf16_results_are_rounded_once_from_fp64():
+    # Sums that need more than fp32's 24 bits and sit next to a bf16 midpoint: rounding the fp64
+    # sum to fp32 first lands exactly on the midpoint and the tie then goes the other way.
+    # 1 + 2^-8 + 2^-30 is above the midpoint of 0x3F80/0x3F81; 1 + 2^-7 + 2^-8 - 2^-30 is below the
+    # midpoint of 0x3F81/0x3F82.  Expected bit patterns written out by hand.
+    one = np.ones(3, np.float32)
+    up = np.array([1.0, 2.0 ** -8, 2.0 ** -30], np.float32)
+    down = np.array([1.0 + 2.0 ** -7, 2.0 ** -8, -(2.0 ** -30)], np.float32)
+    assert unbf(bf(up)).tolist() == up.tolist() and unbf(bf(down)).tolist() == down.tolist()   # inputs are bf16 values
+    W = np.concatenate([bf(up), bf(down)])
+    got = oracle.run_op("gemv", "bf16", [W, bf(one)], 2, rows=1, cols=3)
+    assert got.tolist() == [0x3F81, 0x3F81]
+
+
 def test_gemv_against_torch_fp64():
     rng = np.random.Generator(np.random.PCG64(13))
     N, K, R = 48, 96, 5
