@@ -456,6 +456,14 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
 }
 
 // ---- GEMV ------------------------------------------------------------------------------------------
+// Ask for every kernel argument in one batch of scalar loads.  Left alone, the compiler fetches `n`
+// for the early-exit test first and the pointers only behind it: two dependent trips to the kernel
+// argument buffer (cold in the scalar cache at every launch) before the first weight load goes out,
+// about 0.4 us on a 3 us kernel.
+__device__ __forceinline__ void args_up_front(const GemvArgs& p) {
+    asm volatile("" ::"s"(p.out), "s"(p.W), "s"(p.h), "s"(p.rows), "s"(p.n), "s"(p.cols), "s"(p.row_groups));
+}
+
 // Memory-bound: every weight is read exactly once.  One wave computes R output columns (R weight
 // rows): per chunk of 4 * 64 vectors of the row it issues all R * 4 weight loads (non-temporal:
 // streamed, no reuse) and the 4 loads of its slice of h before the first multiply, accumulates in
@@ -516,6 +524,7 @@ __device__ __forceinline__ void gemv_body(const T* W, const T* h, T* y, int n, i
 
 template <typename T, int IND, int R, int RS>
 __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
+    args_up_front(p);
     const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
     const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
     T* y = static_cast<T*>(p.out);
@@ -586,6 +595,7 @@ __device__ __forceinline__ void gemvb_body(const T* W, const T* h, T* y, int row
 
 template <typename T, int IND, int R, int RB, int RS>
 __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
+    args_up_front(p);
     const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
     const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
     T* y = static_cast<T*>(p.out);
