@@ -230,6 +230,7 @@ pg_status validate(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, i
             const long long ch = numel_in[1];
             if (d.n <= 0 || d.inner <= 0 || d.inner > 0xffffffffll || ch > 0xffffffffll) return fail(PG_EINVAL, "kernel %d: bad n/inner", i);
             if (numel_in[2] != ch) return fail(PG_EINVAL, "kernel %d: scale and bias sizes differ", i);
+            if (ch <= 0 || d.inner > d.n / ch) return fail(PG_EINVAL, "kernel %d: channels*inner exceeds n", i);   // also keeps the product in range
             if (d.n % (ch * d.inner) != 0) return fail(PG_EINVAL, "kernel %d: n is not a multiple of channels*inner", i);
             need[0] = d.n; need[1] = ch; need[2] = ch; out_need = d.n;
             break;
@@ -677,12 +678,7 @@ const char* pg_version(void) { return "pygraph_hip 0.1 (gfx950)"; }
 pg_status pg_chain_workspace_bytes(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor_desc* ext, int32_t n_ext,
                                    const pg_tensor_desc* ints, int32_t n_int, size_t* bytes_out) {
     if (!bytes_out) return fail(PG_EINVAL, "null bytes_out");
-    // weights are not needed for the layout; validate operand references against what we have
-    int max_w = -1;
-    if (kernels && nk > 0)
-        for (int i = 0; i < nk; i++)
-            for (int j = 0; j < 3; j++)
-                if (kernels[i].in[j].kind == PG_REF_WEIGHT) max_w = std::max(max_w, kernels[i].in[j].index);
+    // weights are not needed for the layout: only what the layout reads is checked here, pg_chain_build checks the rest
     if (!kernels || nk <= 0) return fail(PG_EINVAL, "no kernels");
     if (n_ext < 0 || n_int <= 0 || (n_ext && !ext) || !ints) return fail(PG_EINVAL, "bad tensor descriptor arrays");
     for (int i = 0; i < nk; i++) {
@@ -693,9 +689,8 @@ pg_status pg_chain_workspace_bytes(const pg_kernel_desc* kernels, int32_t nk, co
             if (kernels[i].in[j].kind == PG_REF_EXT && (kernels[i].in[j].index < 0 || kernels[i].in[j].index >= n_ext))
                 return fail(PG_EINVAL, "kernel %d: external reference out of range", i);
     }
-    for (int i = 0; i < n_ext; i++) if (ext[i].numel <= 0 || (ext[i].dtype != PG_F32 && ext[i].dtype != PG_BF16)) return fail(PG_EINVAL, "ext %d: bad descriptor", i);
-    for (int i = 0; i < n_int; i++) if (ints[i].numel <= 0 || (ints[i].dtype != PG_F32 && ints[i].dtype != PG_BF16)) return fail(PG_EINVAL, "int %d: bad descriptor", i);
-    (void)max_w;
+    for (int i = 0; i < n_ext; i++) if (ext[i].numel <= 0 || ext[i].numel > (1ll << 40) || (ext[i].dtype != PG_F32 && ext[i].dtype != PG_BF16)) return fail(PG_EINVAL, "ext %d: bad descriptor", i);
+    for (int i = 0; i < n_int; i++) if (ints[i].numel <= 0 || ints[i].numel > (1ll << 40) || (ints[i].dtype != PG_F32 && ints[i].dtype != PG_BF16)) return fail(PG_EINVAL, "int %d: bad descriptor", i);
     Layout L;
     make_layout(kernels, nk, ext, n_ext, ints, n_int, nullptr, L);
     *bytes_out = L.total;
@@ -762,9 +757,9 @@ pg_status pg_capture(pg_chain* c, void* hip_stream) {
     if (!c->staging && !c->ext.empty()) {
         c->staging_stride = align_up(c->ext.size() * 8);
         PG_HIP(hipHostMalloc(&c->staging, c->staging_stride * pg_chain::kRing, hipHostMallocDefault));
-        PG_HIP(hipEventCreateWithFlags(&c->ring_ev[0], hipEventDisableTiming));
-        PG_HIP(hipEventCreateWithFlags(&c->ring_ev[1], hipEventDisableTiming));
     }
+    for (auto& e : c->ring_ev)
+        if (!e && !c->ext.empty()) PG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     for (auto& sg : c->seg) {
         pg_status st = capture_segment(c, sg, kGraphCopy, 0, s, &sg.g_copy, &sg.x_copy);
         if (st) { destroy_graphs(c); return st; }

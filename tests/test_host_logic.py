@@ -150,6 +150,7 @@ BAD = {
     "rmsnorm n != cols": lambda s: _mutate(s, 1, n=3),
     "zero rows": lambda s: _mutate(s, 2, rows=0),
     "sbr n not a multiple of channels*inner": lambda s: _mutate(s, 5, inner=3),
+    "sbr channels*inner far beyond n": lambda s: _mutate(s, 5, inner=0xffffffff),
     "segment goes backwards": lambda s: _mutate(s, 2, segment=1),
     "segment gap": lambda s: _mutate(s, len(s.kernels) - 1, segment=2),
     "dtype mismatch": lambda s: _mutate(s, 3, dtype="bf16"),
@@ -202,6 +203,10 @@ def test_build_argument_errors():
     assert L.pg_chain_build(ks, len(spec.kernels), ext, len(spec.ext), ints, len(spec.ints), wp, ws, len(spec.weights),
                             0x100000, need.value, None) == 1
     L.pg_chain_destroy(None)                                                          # a no-op
+    # the size query rejects what would overflow its own layout arithmetic
+    huge = dataclasses.replace(spec, ints=[TensorSpec("f32", 1 << 41)] + list(spec.ints[1:]))
+    ks2, ext2, ints2, _ = binding.pack_descriptor(huge)
+    assert L.pg_chain_workspace_bytes(ks2, len(huge.kernels), ext2, len(huge.ext), ints2, len(huge.ints), C.byref(need)) == 1
 
 
 def test_calls_out_of_order_or_with_bad_pointers():
