@@ -537,6 +537,76 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
     else gemv_body<T, R, RS, false>(W, h, y, p.n, p.cols, j0, lane);
 }
 
+// The same for rows of exactly one chunk (2048 bf16 or 1024 fp32 columns -- the decode chain's shape)
+// and one or two rows of h: instead of every wave fetching all of h, lane t of the workgroup fetches
+// vector t of each row once and the four waves share it through LDS.  That takes 12 KB (one row of h)
+// or 24 KB (two) of cache traffic per workgroup off the load path the weights come in by (3.16 ->
+// 3.07 us per launch at 2048 x 2048, one row); h is asked for before the weights, so the exchange is
+// over long before the first weight arrives.  Same lanes, same products, same order as gemv_body and
+// gemvb_body: the results are bit-identical.
+static_assert(kBlock == 64 * kGemvChunk, "one vector of h per lane of the workgroup");
+template <typename T, int R, int RB, bool AL>
+__device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */) {
+    constexpr int NV = Vec<T, 16>::NV;
+    constexpr int kCols = 64 * kGemvChunk * NV;
+    unsigned hv[RB][4], ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4];
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++) load_vec<T, 16, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
+    __builtin_amdgcn_sched_barrier(0);   // h first: loads come back in the order they were issued
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        const T* wrow = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * kCols;   // a ragged last group re-reads the last row
+#pragma unroll
+        for (int u = 0; u < kGemvChunk; u++) load_vec<T, 16, AL, true>(wrow + (size_t)(u * 64 + lane) * NV, ww[r][u]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++) {
+        v4u t;
+        t.x = hv[rr][0]; t.y = hv[rr][1]; t.z = hv[rr][2]; t.w = hv[rr][3];
+        hs[rr * kBlock + tid] = t;
+    }
+    __syncthreads();      // every wave of the workgroup gets here: none leaves early
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++)
+#pragma unroll
+        for (int u = 0; u < kGemvChunk; u++) {
+            const v4u t = hs[rr * kBlock + u * 64 + lane];
+            wh[rr][u][0] = t.x; wh[rr][u][1] = t.y; wh[rr][u][2] = t.z; wh[rr][u][3] = t.w;
+        }
+    float acc[R][RB];
+#pragma unroll
+    for (int r = 0; r < R; r++)
+#pragma unroll
+        for (int rr = 0; rr < RB; rr++) {
+            acc[r][rr] = 0.f;
+#pragma unroll
+            for (int u = 0; u < kGemvChunk; u++) acc[r][rr] = dot_acc<T>(ww[r][u], wh[rr][u], acc[r][rr]);
+        }
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++)
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            const float s = wave_sum(acc[r][rr]);
+            if (lane == 0 && j0 + r < n) store_elem(y + (size_t)rr * n + j0 + r, s);
+        }
+}
+
+// RB = rows of h: 1 or 2
+template <typename T, int IND, int R, int RB>
+__global__ __launch_bounds__(kBlock) void k_gemv_shared(GemvArgs p) {
+    args_up_front(p);
+    const T* W = static_cast<const T*>(resolve<(IND & 1) != 0>(p.W));
+    const T* h = static_cast<const T*>(resolve<(IND & 2) != 0>(p.h));
+    T* y = static_cast<T*>(p.out);
+    __shared__ v4u hs[RB * kBlock];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int j0 = (blockIdx.x * (kBlock / 64) + (tid >> 6)) * R;
+    const bool al = aligned_to(W, 16) && aligned_to(h, 16);
+    if (al) gemv_body_shared<T, R, RB, true>(W, h, y, p.n, j0, lane, tid, hs);
+    else gemv_body_shared<T, R, RB, false>(W, h, y, p.n, j0, lane, tid, hs);
+}
+
 // Batched (rows > 1) on the vector units: one wave per R output columns, as in the one-row kernel;
 // the R weight chunks stay in registers while the rows of h (from cache) stream past them,
 // RB rows at a time (RB = 2 when there are only two rows: a clamped row would be loaded and summed
@@ -1058,18 +1128,31 @@ const void* gemvb_by_ind(int ind) {
     }
 }
 
+template <typename T, int RB>
+const void* gemv_shared_by_ind(int ind) {
+    switch (ind) {
+    case 0: return PG_FN(k_gemv_shared<T, 0, 2, RB>);
+    case 1: return PG_FN(k_gemv_shared<T, 1, 2, RB>);
+    case 2: return PG_FN(k_gemv_shared<T, 2, 2, RB>);
+    case 3: return PG_FN(k_gemv_shared<T, 3, 2, RB>);
+    default: return nullptr;
+    }
+}
+
 template <typename T, int RS>
-bool plan_gemv_rs(int ind, int rows, int n, Launch* out) {
+bool plan_gemv_rs(int ind, int rows, int n, int cols, Launch* out) {
     out->block = dim3(kBlock);
+    const bool one_chunk = RS == 0 && cols == 64 * kGemvChunk * (16 / (int)sizeof(T));   // the forms that share h through LDS
     if (rows == 1 && n >= 1024) {
         // two weight rows per wave once there are enough rows to fill the chip with half the waves
-        out->fn = gemv_by_ind<T, 2, RS>(ind);
+        out->fn = one_chunk ? gemv_shared_by_ind<T, 1>(ind) : gemv_by_ind<T, 2, RS>(ind);
         out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
     } else if (rows == 1) {
         out->fn = gemv_by_ind<T, 1, RS>(ind);
         out->grid = dim3(blocks_for(n, kBlock / 64));
     } else if (n >= 1024) {
-        out->fn = rows == 2 ? gemvb_by_ind<T, 2, 2, RS>(ind) : gemvb_by_ind<T, 2, 4, RS>(ind);
+        if (one_chunk && rows <= 4) out->fn = rows == 2 ? gemv_shared_by_ind<T, 2>(ind) : rows == 3 ? gemv_shared_by_ind<T, 3>(ind) : gemv_shared_by_ind<T, 4>(ind);
+        else out->fn = rows == 2 ? gemvb_by_ind<T, 2, 2, RS>(ind) : gemvb_by_ind<T, 2, 4, RS>(ind);
         out->grid = dim3(blocks_for(n, (kBlock / 64) * 2));
     } else {
         out->fn = rows == 2 ? gemvb_by_ind<T, 1, 2, RS>(ind) : gemvb_by_ind<T, 1, 4, RS>(ind);
@@ -1104,11 +1187,13 @@ template <typename T>
 bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
     constexpr int NV = 16 / (int)sizeof(T);
     if constexpr (sizeof(T) == 2) {
-        // A dense contraction: matrix cores from 5 rows on, and from 3 rows on where the narrow form
-        // applies (measured at 2048 x 2048: 2 rows 3.8 us on the vector units against 3.9 us, 4 rows
-        // 4.5 against 4.1 us).
+        // A dense contraction: matrix cores from 5 rows on, and for 3 and 4 rows where the narrow form
+        // applies and the vector form that shares h through LDS does not (measured at 2048 x 2048, us
+        // per launch at 2 / 3 / 4 rows: vector with shared h 3.3 / 3.5 / 3.7, narrow matrix-core form
+        // 3.9 / 4.0 / 4.0, vector with h per wave 3.8 / 4.4 / 4.5).
         const bool narrow_ok = rows <= 16 && cols <= 32 * 4 * kMmSteps && n >= 16;
-        if (cols % 8 == 0 && (rows > 4 || (rows >= 3 && narrow_ok))) {
+        const bool shared_ok = rows <= 4 && n >= 1024 && cols == 64 * kGemvChunk * NV;
+        if (cols % 8 == 0 && (rows > 4 || (rows >= 3 && narrow_ok && !shared_ok))) {
             out->block = dim3(kBlock);
             // row groups of 16-row tiles: enough workgroups to fill the chip twice over at most
             const int ntiles = (rows + 15) / 16;
@@ -1136,9 +1221,9 @@ bool plan_gemv(int ind, int rows, int n, int cols, Launch* out) {
             return out->fn != nullptr;
         }
     }
-    if (cols % (64 * kGemvChunk * NV) == 0) return plan_gemv_rs<T, 0>(ind, rows, n, out);
-    if (cols % NV == 0) return plan_gemv_rs<T, 1>(ind, rows, n, out);
-    return plan_gemv_rs<T, 2>(ind, rows, n, out);
+    if (cols % (64 * kGemvChunk * NV) == 0) return plan_gemv_rs<T, 0>(ind, rows, n, cols, out);
+    if (cols % NV == 0) return plan_gemv_rs<T, 1>(ind, rows, n, cols, out);
+    return plan_gemv_rs<T, 2>(ind, rows, n, cols, out);
 }
 
 template <typename T, bool VEC, int U, typename IdxT>

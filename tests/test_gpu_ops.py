@@ -134,7 +134,10 @@ def test_rmsnorm(dtype, rows, cols, off):
                                          (40, 48, 4096), (100, 33, 2048), (64, 2048, 2048), (20, 16, 2056), (72, 24, 8200), (8, 64, 2048),
                                          # one tile of rows: 8 columns per workgroup, with and without the upper half of the tile
                                          (16, 2048, 2048), (12, 100, 1024), (9, 20, 2048), (6, 16, 2040), (7, 27, 8), (3, 64, 2048), (4, 100, 512),
-                                         (4, 15, 2048), (3, 40, 4096)])
+                                         (4, 15, 2048), (3, 40, 4096),
+                                         # one row of exactly one chunk (h shared through LDS): ragged last workgroup, odd n
+                                         (1, 1027, 2048), (1, 1030, 1024), (1, 4096, 2048), (2, 2048, 2048), (2, 1029, 2048), (2, 1030, 1024),
+                                         (3, 1024, 2048), (4, 2048, 2048), (4, 1100, 1024), (3, 1031, 1024)])
 def test_gemv(dtype, rows, n, cols):
     say(f"gemv {dtype} rows={rows} n={n} cols={cols}")
     rng = np.random.Generator(np.random.PCG64(300 + cols + n))
@@ -152,6 +155,21 @@ def test_gemv(dtype, rows, n, cols):
         Wi, hi = f32_to_bf16_bits(Wi), f32_to_bf16_bits(hi)
     got = run_single(spec, [hi], [Wi], None, "gemv int")
     assert same_bits(got, oracle.run_chain(spec, [Wi], [hi])[0])
+
+
+@pytest.mark.parametrize("dtype,rows,n,cols,off", [("bf16", 1, 2048, 2048, 2), ("bf16", 1, 1100, 2048, 6), ("f32", 1, 1024, 1024, 4),
+                                                   ("bf16", 8, 64, 2048, 2), ("bf16", 40, 48, 2048, 10), ("bf16", 2, 1024, 2048, 2), ("bf16", 4, 1024, 2048, 14)])
+def test_gemv_with_a_misaligned_activation(dtype, rows, n, cols, off):
+    # h sits `off` bytes past a 16-byte boundary: every form fetches it by element loads, same lanes, same order
+    say(f"gemv misaligned {dtype} rows={rows} n={n} cols={cols} off={off}")
+    rng = np.random.Generator(np.random.PCG64(350 + n + off))
+    W = draw(rng, n * cols, dtype, 0.02)
+    hh = draw(rng, rows * cols, dtype)
+    k = KernelSpec("gemv", dtype, 0, (Ref(WEIGHT, 0), Ref(EXT, 0)), n, rows=rows, cols=cols)
+    spec = ChainSpec("g", [k], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, rows * n)], [TensorSpec(dtype, n * cols)], [0])
+    got = run_single(spec, [hh], [W], [off], "gemv misaligned")
+    assert same_bits(got, run_single(spec, [hh], [W], [0], "gemv aligned"))
+    assert_close(got, oracle.run_chain(spec, [W], [hh])[0], dtype, "gemv", rtol=(1e-5 if dtype == "f32" else 2.0 ** -7))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
