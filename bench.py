@@ -142,7 +142,7 @@ def main() -> int:
     gchain.close()
     gemv_bytes = H * H * 2 + H * 2 + H * 2       # bf16 weight matrix + input vector + output vector
     log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s")
-    roofline = {"kernel": "k_gemv<bf16> 2048x2048, batch 1", "bound": "hbm", "achieved": gemv_bytes / gemv_us / 1e3,
+    roofline = {"kernel": "k_gemv_shared<bf16> 2048x2048, batch 1", "bound": "hbm", "achieved": gemv_bytes / gemv_us / 1e3,
                 "peak": HBM_PEAK, "unit": "GB/s", "frac": gemv_bytes / gemv_us / 1e3 / HBM_PEAK,
                 "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": reps * n_gemv,
                 "how": "HIP events on the launch stream around 50 replays of a graph of the chain's 120 GEMV launches; per-launch time includes the inter-kernel dispatch gap",
