@@ -237,6 +237,9 @@ pg_status pg_chain_output(const pg_chain *chain, int32_t int_index, void **dev_p
 pg_status pg_chain_placeholder(const pg_chain *chain, int32_t ext_index, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_pointer_table(const pg_chain *chain, void **dev_ptr_out, size_t *bytes_out);
 pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);
+/* Launch shape of kernel `kernel` of the chain (workgroups, threads per workgroup): the same in every
+ * replay mode, fixed by the kernel's shape alone at pg_chain_build.  Either output may be NULL. */
+pg_status pg_chain_launch_shape(const pg_chain *chain, int32_t kernel, uint32_t *workgroups_out, uint32_t *threads_out);
 pg_status pg_set_table_refresh(pg_chain *chain, int32_t how /* pg_table_refresh */);
 pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */);
 /* Destroys the graphs and host objects.  The caller has synchronised every stream the chain ran on;

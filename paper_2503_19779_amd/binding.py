@@ -82,6 +82,7 @@ def lib():
         L.pg_chain_placeholder.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.pg_chain_pointer_table.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.pg_chain_stats.argtypes = [vp, C.POINTER(_Stats)]
+        L.pg_chain_launch_shape.argtypes = [vp, i32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
         L.pg_set_table_refresh.argtypes = [vp, i32]
         L.pg_set_copy_refresh.argtypes = [vp, i32]
         L.pg_chain_destroy.argtypes = [vp]
@@ -344,6 +345,12 @@ class Chain:
         s = _Stats()
         _check(lib().pg_chain_stats(self._h, C.byref(s)))
         return {f: getattr(s, f) for f, _ in _Stats._fields_}
+
+    def launch_shape(self, kernel: int):
+        """(workgroups, threads per workgroup) of one kernel of the chain."""
+        g, b = C.c_uint32(), C.c_uint32()
+        _check(lib().pg_chain_launch_shape(self._h, kernel, C.byref(g), C.byref(b)))
+        return g.value, b.value
 
     def output(self, i: int) -> np.ndarray:
         """Internal buffer i as numpy (float32, or uint16 bf16 bit patterns); synchronises."""

@@ -1067,6 +1067,13 @@ pg_status pg_chain_stats(const pg_chain* c, pg_stats* out) {
     return PG_OK;
 }
 
+pg_status pg_chain_launch_shape(const pg_chain* c, int32_t kernel, uint32_t* workgroups_out, uint32_t* threads_out) {
+    if (!c || kernel < 0 || kernel >= (int)c->rec.size()) return fail(PG_EINVAL, "bad kernel index");
+    if (workgroups_out) *workgroups_out = c->rec[kernel].direct.grid.x;
+    if (threads_out) *threads_out = c->rec[kernel].direct.block.x;
+    return PG_OK;
+}
+
 pg_status pg_set_table_refresh(pg_chain* c, int32_t how) {
     if (!c || how < PG_TABLE_KERNARG || how > PG_TABLE_HOST) return fail(PG_EINVAL, "bad table refresh kind");
     c->table_how = how;

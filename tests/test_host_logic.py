@@ -244,3 +244,35 @@ def test_calls_out_of_order_or_with_bad_pointers():
     ch.set_copy_refresh(pg.COPY_MEMCPY)
     ch.set_copy_refresh(pg.COPY_KERNEL)
     ch.close()
+
+
+# ------------------------------------------------------------------ launch shapes (host only)
+def _gemv_chain(dtype, rows, n, cols):
+    k = KernelSpec("gemv", dtype, 0, (Ref(WEIGHT, 0), Ref(EXT, 0)), n, rows=rows, cols=cols)
+    return ChainSpec("g", [k], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, rows * n)], [TensorSpec(dtype, n * cols)], [0])
+
+
+@pytest.mark.parametrize("rows,want", [(1, 256), (2, 256), (4, 256), (8, 256), (16, 256), (32, 256), (64, 256), (128, 256), (48, 384)])
+def test_decode_gemv_fills_the_chip_at_every_bucket(rows, want):
+    """The 2048 x 2048 bf16 GEMV is laid out over at least one workgroup per CU (256) at every batch
+    size: weight streaming needs every CU pulling (the shape is fixed on the host, so no GPU is needed
+    to check it)."""
+    ch = pg.Chain.host_only(_gemv_chain("bf16", rows, 2048, 2048))
+    assert ch.launch_shape(0) == (want, 256)
+    ch.close()
+
+
+def test_launch_shapes_of_other_kernels_and_bad_index():
+    ch = pg.Chain.host_only(decode_chain())
+    shapes = {k.op: ch.launch_shape(i) for i, k in enumerate(ch.spec.kernels)}
+    assert shapes["rmsnorm"] == (1, 256) and shapes["add"] == (1, 256) and shapes["gelu"] == (4, 256) and shapes["gemv"] == (256, 256)
+    with pytest.raises(pg.PgError):
+        ch.launch_shape(len(ch.spec.kernels))
+    with pytest.raises(pg.PgError):
+        ch.launch_shape(-1)
+    ch.close()
+    # small and ragged GEMVs: one wave per weight row, or 8 columns per workgroup on the matrix cores
+    for (rows, n, cols), want in (((1, 5, 24), 2), ((1, 130, 2056), 33), ((5, 33, 520), 5), ((9, 64, 4096), 4), ((100, 33, 2048), 8), ((40, 48, 4096), 9)):
+        c2 = pg.Chain.host_only(_gemv_chain("bf16", rows, n, cols))
+        assert c2.launch_shape(0) == (want, 256), (rows, n, cols, c2.launch_shape(0))
+        c2.close()
