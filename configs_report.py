@@ -1,6 +1,6 @@
 """Timing report for the benchmark chains other than the one bench.py times:
 
-    python -m paper_2503_19779_amd.configs_report --config 0 1 3 4 5
+    python configs_report.py --config 0 1 3 4 5
 
 (config 0 is the launch floor: 512 dependent kernels on 64 elements each; 6 sweeps the batch-1
 GEMV over matrix sizes; 7 is the decode chain read literally; 8 the GEMV at every batch size;

@@ -86,7 +86,10 @@ int orc_chain_run(const orc_kernel *k, int32_t k_begin, int32_t k_end,
 
 /* Selection: for each segment the available variant of least cost; cost is [n_seg][3] in the
  * order eager, graph-copy, graph-indirect; NaN or +inf marks a variant that does not exist.
- * Ties keep the earlier variant.  Returns 0, or -(s+1) if segment s has no variant. */
+ * Ties keep the earlier variant.  Returns 0, or -(s+1) if segment s has no variant.
+ * Costs are durations: the rule is stated for finite costs >= 0.  A negative finite cost is outside
+ * its domain -- this routine simply compares it like any other number, the product's pg_select
+ * refuses such a table as malformed -- so the two are compared on non-negative tables only. */
 int orc_select(const double *cost, int32_t n_seg, uint8_t *mode_out);
 
 #ifdef __cplusplus

@@ -7,7 +7,6 @@ form of `pg_workloads.spec` (duck-typed; nothing is imported from there).
 from __future__ import annotations
 
 import ctypes as C
-import os
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -56,11 +55,12 @@ _lib = None
 
 
 def lib():
-    """Load the HIP library; build it first only if it has never been built.  No fallback exists."""
+    """Load the HIP library; build it first if it is missing or was built from other sources than the
+    tree's (compared by content hash, so a copied tree with fresh file times does not rebuild).  No
+    fallback exists: if it can be neither loaded nor built this raises."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
-            _build.build_library(force=True)
+        _build.build_library(force=False)
         L = C.CDLL(_build.LIB)
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         KP, TP = C.POINTER(_KernelDesc), C.POINTER(_TensorDesc)

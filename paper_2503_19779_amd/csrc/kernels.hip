@@ -592,7 +592,7 @@ __device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, i
         }
 }
 
-// RB = rows of h: 1 or 2
+// RB = rows of h: 1 to 4
 template <typename T, int IND, int R, int RB>
 __global__ __launch_bounds__(kBlock) void k_gemv_shared(GemvArgs p) {
     args_up_front(p);
@@ -718,7 +718,7 @@ __device__ __forceinline__ int mm_k0(int s0, int wave, int l) {
 template <bool FULL, bool AL, int NR = 16>
 __device__ __forceinline__ void mm_load_rows(const bf16_t* h, int rows, int cols, int r0, int s0, int wave, int lane, unsigned (*g)[4]) {
     const int k0 = mm_k0(s0, wave, lane);
-    const int koff = (FULL || k0 < cols) ? k0 : 0;      // an out-of-range chunk meets a zero weight fragment
+    const int koff = (FULL || k0 < cols) ? k0 : 0;      // an out-of-range chunk is read from column 0 and zeroed on both sides later
 #pragma unroll
     for (int r = 0; r < NR; r++) {
         const int R = r0 + r < rows ? r0 + r : rows - 1;
@@ -743,7 +743,8 @@ __device__ __forceinline__ void mm_read_frags(const char* lds, int lane, v4u* f)
     for (int i = 0; i < kMmSteps; i++)
         f[i] = *reinterpret_cast<const v4u*>(lds + (i * 4 + (lane >> 4)) * kMmSlotBytes + (lane & 15) * 16);
 }
-// chunks beyond cols: the weight side is zeroed, the h side may then hold anything
+// chunks beyond cols are zeroed on both sides (the loads fetched column 0 in their place): zeroing the
+// weight side alone would turn an Inf or NaN of h[:, 0:8] into NaN in every output (0 * Inf)
 template <bool FULL>
 __device__ __forceinline__ void mm_zero_tail(v4u* b, int cols, int s0, int wave, int kq) {
     if constexpr (!FULL) {
@@ -808,6 +809,7 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         mm_stage(lds, lane, g);
         mm_read_frags(lds, lane, a);
+        mm_zero_tail<FULL>(a, cols, 0, wave, kq);
         if (t1 - t0 > 1) mm_load_rows<FULL, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
         mm_stage(lds, lane, gw);
         mm_read_frags(lds, lane, b);
@@ -821,6 +823,7 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
             mm_stage(lds, lane, g);
             if (t + 1 < t1) mm_load_rows<FULL, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
             mm_read_frags(lds, lane, a);
+            mm_zero_tail<FULL>(a, cols, 0, wave, kq);
             __builtin_amdgcn_sched_barrier(0);
             mm_mfma(a, b, acc);
             mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
@@ -835,6 +838,7 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
                 mm_load_rows<FULL, AL>(W, n, cols, j0, s0, wave, lane, gw);
                 mm_stage(lds, lane, g);
                 mm_read_frags(lds, lane, a);
+                mm_zero_tail<FULL>(a, cols, s0, wave, kq);
                 mm_stage(lds, lane, gw);
                 mm_read_frags(lds, lane, b);
                 mm_zero_tail<FULL>(b, cols, s0, wave, kq);
@@ -867,6 +871,7 @@ __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf1
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     mm_stage<NRH>(lds, lane, g);
     mm_read_frags(lds, lane, a);
+    mm_zero_tail<FULL>(a, cols, 0, wave, kq);
     mm_stage<8>(lds, lane, gw);
     mm_read_frags(lds, lane, b);
     mm_zero_tail<FULL>(b, cols, 0, wave, kq);

@@ -126,3 +126,55 @@ def check_all_modes(h: Harness, t: int, dtype: str, what: str, rtol=None, out_nu
         assert same_bits(e, i), f"{what}: eager and graph-indirect differ (output {oi}, iteration {t})"
         worst = max(worst, assert_close(e, want[oi][:n], dtype, f"{what} output {oi} iteration {t}", rtol))
     return worst
+
+
+def stepwise_check(h, x_np, x_dev, rows=None, rtol=None, kernels=None, stats=None):
+    """Run the chain one kernel at a time; compare each kernel's output, element by element, with the
+    oracle's single-op routine applied to the inputs that GPU kernel actually read.  `x_dev` may hold
+    tensors or raw device addresses.  `rows`: for chains whose buffers are all [B, H] row-major with
+    row-independent ops, check only these rows (keeps the oracle affordable).  `kernels`: compare only
+    these kernel indices (all are run).  `rtol` None = the stated tolerance of the kernel's dtype.
+    `stats`, if a dict, receives `flip_kernels` / `flip_elements`: kernels / elements whose bits differ
+    from the oracle's (a chain with none is bit-identical to the oracle's own run, by induction).
+    Returns the worst error / tolerance ratio."""
+    spec, c = h.spec, h.chain
+    worst, flip_k, flip_e = 0.0, 0, 0
+    for k, kk in enumerate(spec.kernels):
+        compare = kernels is None or k in kernels
+        ins = []
+        if compare:
+            for r in kk.ins:
+                if r.kind == "ext":
+                    ins.append(x_np[r.index])
+                elif r.kind == "weight":
+                    ins.append(h.w_np[r.index])
+                else:
+                    ins.append(c.output(r.index))
+        c.eager_range(x_dev, k, k + 1, h.stream)
+        h.stream.synchronize()
+        if not compare:
+            continue
+        got = c.output(kk.out)
+        if rows is not None:
+            B = spec.meta["batch"]
+            Hh = spec.meta["hidden"]
+            sel = lambda a: a.reshape(B, Hh)[rows].reshape(-1)
+            if kk.op == "rmsnorm":
+                want = oracle.run_op("rmsnorm", kk.dtype, [sel(ins[0]), ins[1]], kk.n, rows=len(rows), cols=kk.cols, eps=kk.eps)
+            elif kk.op == "gemv":
+                want = oracle.run_op("gemv", kk.dtype, [ins[0], sel(ins[1])], kk.n, rows=len(rows), cols=kk.cols)
+            elif kk.op == "gelu":
+                want = oracle.run_op("gelu", kk.dtype, [sel(ins[0])], len(rows) * Hh)
+            else:
+                want = oracle.run_op(kk.op, kk.dtype, [sel(ins[0]), sel(ins[1])], len(rows) * Hh)
+            got = sel(got[:B * Hh])
+        else:
+            want = oracle.run_op(kk.op, kk.dtype, ins, kk.n, kk.m, kk.rows, kk.cols, kk.inner, kk.channels, kk.eps)
+            got = got[:want.size]
+        worst = max(worst, assert_close(got, want, kk.dtype, f"kernel {k} ({kk.op})", rtol))
+        nd = int(np.count_nonzero(as_f64(got) != as_f64(want)))      # +0 and -0 count as equal
+        flip_k += nd > 0
+        flip_e += nd
+    if stats is not None:
+        stats["flip_kernels"], stats["flip_elements"] = flip_k, flip_e
+    return worst

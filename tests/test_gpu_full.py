@@ -12,53 +12,12 @@ import torch
 
 import oracle
 import paper_2503_19779_amd as pg
-from gpu_util import Harness, assert_close, check_all_modes, same_bits, say, as_f64, tol_bf16
+from gpu_util import Harness, assert_close, check_all_modes, same_bits, say, as_f64, tol_bf16, stepwise_check
 from paper_2503_19779_amd.binding import to_device, to_numpy
 from pg_workloads import (decode_chain, decode_buckets, bucket_sequence, refresh_stress_chain, large_tensor_chain,
                           make_inputs, make_weights)
 
 pytestmark = pytest.mark.gpu
-
-
-def stepwise_check(h, x_np, x_dev, rows=None, rtol=2.0 ** -7, kernels=None):
-    """Run the chain one kernel at a time; compare each output with the oracle's single-op routine
-    applied to the inputs the GPU kernel actually read.  `rows`: for chains whose buffers are all
-    [B, H] row-major with row-independent ops, check only these rows (keeps the oracle affordable)."""
-    spec, c = h.spec, h.chain
-    worst = 0.0
-    for k, kk in enumerate(spec.kernels):
-        ins = []
-        for r in kk.ins:
-            if r.kind == "ext":
-                ins.append(x_np[r.index])
-            elif r.kind == "weight":
-                ins.append(h.w_np[r.index])
-            else:
-                ins.append(c.output(r.index))
-        c.eager_range(x_dev, k, k + 1, h.stream)
-        h.stream.synchronize()
-        if kernels is not None and k not in kernels:
-            continue
-        got = c.output(kk.out)
-        H = kk.cols if kk.op in ("rmsnorm", "gemv") else None
-        if rows is not None:
-            B = spec.meta["batch"]
-            Hh = spec.meta["hidden"]
-            sel = lambda a: a.reshape(B, Hh)[rows].reshape(-1)
-            if kk.op == "rmsnorm":
-                want = oracle.run_op("rmsnorm", kk.dtype, [sel(ins[0]), ins[1]], kk.n, rows=len(rows), cols=kk.cols, eps=kk.eps)
-            elif kk.op == "gemv":
-                want = oracle.run_op("gemv", kk.dtype, [ins[0], sel(ins[1])], kk.n, rows=len(rows), cols=kk.cols)
-            elif kk.op == "gelu":
-                want = oracle.run_op("gelu", kk.dtype, [sel(ins[0])], len(rows) * Hh)
-            else:
-                want = oracle.run_op(kk.op, kk.dtype, [sel(ins[0]), sel(ins[1])], len(rows) * Hh)
-            got = sel(got[:B * Hh])
-        else:
-            want = oracle.run_op(kk.op, kk.dtype, ins, kk.n, kk.m, kk.rows, kk.cols, kk.inner, kk.channels, kk.eps)
-            got = got[:want.size]
-        worst = max(worst, assert_close(got, want, kk.dtype, f"kernel {k} ({kk.op})", rtol))
-    return worst
 
 
 def end_to_end_stats(g, o):
@@ -69,7 +28,12 @@ def end_to_end_stats(g, o):
 
 
 def test_config2_decode_chain_full():
-    """511 kernels, hidden 2048, batch 1, 1 GB of bf16 weights."""
+    """511 kernels, hidden 2048, batch 1, 1 GB of bf16 weights.  Per iteration: the modes agree bit for
+    bit; every kernel, stepped through, matches the oracle's single-op routine on the inputs it read,
+    element by element at one bf16 ulp (2^-7, tighter than the stated 2e-2); and end to end against the
+    oracle's own run: bit for bit when no kernel's rounding differed from the oracle's on the way (then
+    the two runs are the same by induction), else -- a deep bf16 chain re-rounds a flipped bit 500 times
+    over -- the stated elementwise bound on all but 1 % of the elements, with rel-L2 <= 2e-2."""
     say("config 2: generating weights")
     spec = decode_chain()
     h = Harness(spec)
@@ -84,20 +48,22 @@ def test_config2_decode_chain_full():
         assert same_bits(outs["eager"], outs["copy"]) and same_bits(outs["eager"], outs["indirect"]), t
         want = h.oracle(x_np)[0]
         st = end_to_end_stats(outs["eager"], want)
-        say(f"config 2 iteration {t}: end to end {st}")
-        # full depth: aggregate bounds (a handful of elements may sit a few bf16 ulps off after 511 roundings)
-        assert st["rel_l2"] <= 2e-2 and st["p99_ratio"] <= 1.0 and st["max_ratio"] <= 4.0
+        flips = {}
+        h.scrub()
+        worst = stepwise_check(h, x_np, x_dev, rtol=2.0 ** -7, stats=flips)
+        assert same_bits(h.chain.output(0), outs["eager"]), t      # stepping through == one replay
+        say(f"config 2 iteration {t}: step by step worst error / tolerance(2^-7) = {worst:.3f}, "
+            f"kernels whose rounding differs from the oracle's: {flips['flip_kernels']} ({flips['flip_elements']} elements); end to end {st}")
+        if flips["flip_kernels"] == 0:
+            assert st["frac_differ"] == 0.0, "no kernel differed from the oracle, yet the final outputs do"
+        else:
+            assert st["rel_l2"] <= 2e-2 and st["p99_ratio"] <= 1.0 and st["max_ratio"] <= 4.0
         # first two layers: the stated elementwise bound
         h.scrub()
         h.chain.eager_range(x_dev, 0, 48, h.stream)
         h.stream.synchronize()
         want48 = oracle.run_chain(prefix, h.w_np, x_np)[0]
         assert_close(h.chain.output(0), want48, "bf16", f"first 48 kernels, iteration {t}")
-    x_np, x_dev = h.inputs(0)
-    worst = stepwise_check(h, x_np, x_dev)
-    say(f"config 2 step by step, all 511 kernels: worst error / tolerance(2^-7) = {worst:.3f}")
-    final = h.chain.output(0)
-    assert same_bits(final, h.run("indirect", x_dev)[0])      # stepping through == one replay
     h.close()
 
 
@@ -179,8 +145,9 @@ def test_config5_buckets():
             outs[mode] = h.run(mode, x_dev)[0]
         assert same_bits(outs["eager"], outs["copy"]) and same_bits(outs["eager"], outs["indirect"]), B
         rows = sorted(rng.choice(B, min(B, 2), replace=False).tolist())
-        ks = set(range(0, 24)) | set(range(250, 262)) | set(range(499, 511))
-        worst = stepwise_check(h, x_np, x_dev, rows=rows, kernels=ks)
+        # every GEMV of the chain (the kernel whose form changes with the bucket), and all kernels of three stretches
+        ks = {k for k, kk in enumerate(h.spec.kernels) if kk.op == "gemv"} | set(range(0, 24)) | set(range(250, 262)) | set(range(499, 511))
+        worst = stepwise_check(h, x_np, x_dev, rows=rows, rtol=2.0 ** -7, kernels=ks)
         # rows are independent: a row of the batched run equals the same row run alone (oracle, 2 layers)
         sub = decode_chain(batch=len(rows), seed=h.spec.seed).truncated(48, outputs=[0])
         x_sub = [x.reshape(B, -1)[rows].reshape(-1) for x in x_np]

@@ -157,6 +157,31 @@ def test_gemv(dtype, rows, n, cols):
     assert same_bits(got, oracle.run_chain(spec, [Wi], [hi])[0])
 
 
+@pytest.mark.parametrize("rows,n,cols", [(1, 64, 520), (2, 40, 520), (5, 33, 520), (40, 48, 520), (20, 16, 2056), (72, 24, 8200), (9, 20, 2048)])
+def test_gemv_propagates_non_finite_activations_like_the_oracle(rows, n, cols):
+    """An Inf and a NaN among the first columns of h: every form of the kernel (vector, and the matrix-core
+    forms whose last K chunk is partly beyond cols) yields +-Inf / NaN exactly where the oracle does, and
+    finite values elsewhere."""
+    say(f"gemv non-finite rows={rows} n={n} cols={cols}")
+    rng = np.random.Generator(np.random.PCG64(360 + cols + rows))
+    W = draw(rng, n * cols, "bf16", 0.02)
+    hh = draw(rng, rows * cols, "bf16").reshape(rows, cols)
+    hh[0, 3] = 0x7F80                    # +Inf in row 0
+    if rows > 1:
+        hh[rows - 1, 5] = 0x7FC0         # NaN in the last row
+    hh = hh.reshape(-1)
+    k = KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, 0), Ref(EXT, 0)), n, rows=rows, cols=cols)
+    spec = ChainSpec("g", [k], [TensorSpec("bf16", rows * cols)], [TensorSpec("bf16", rows * n)], [TensorSpec("bf16", n * cols)], [0])
+    got = as_f64(run_single(spec, [hh], [W], None, "gemv non-finite"))
+    want = as_f64(oracle.run_chain(spec, [W], [hh])[0])
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isposinf(got), np.isposinf(want)) and np.array_equal(np.isneginf(got), np.isneginf(want))
+    assert np.isinf(want[:n]).all() and (rows == 1 or np.isnan(want[-n:]).all())
+    fin = np.isfinite(want)
+    if fin.any():
+        assert_close(got[fin].astype(np.float32), want[fin].astype(np.float32), "f32", "finite rows", rtol=2.0 ** -7)
+
+
 @pytest.mark.parametrize("dtype,rows,n,cols,off", [("bf16", 1, 2048, 2048, 2), ("bf16", 1, 1100, 2048, 6), ("f32", 1, 1024, 1024, 4),
                                                    ("bf16", 8, 64, 2048, 2), ("bf16", 40, 48, 2048, 10), ("bf16", 2, 1024, 2048, 2), ("bf16", 4, 1024, 2048, 14)])
 def test_gemv_with_a_misaligned_activation(dtype, rows, n, cols, off):

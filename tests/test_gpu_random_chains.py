@@ -1,14 +1,17 @@
 """GPU parity on randomly structured chains: every op, operand kind, broadcast period, in-place form
 and segmentation the descriptor allows, drawn from a seed.  For each chain: eager, graph-copy,
 graph-indirect, the host-updated graph and a random per-segment mixture give the same bits on fresh
-inputs at fresh (sometimes misaligned) addresses, and match the CPU oracle."""
+inputs at fresh (sometimes misaligned) addresses, and match the CPU oracle: every kernel, stepped
+through, element by element at the stated tolerance against the oracle's single-op routine on the
+inputs it read, and the final outputs in aggregate (a chain of up to 14 kernels amplifies a single
+rounding through cancelling adds, so the end-to-end elementwise error has no bound of its own)."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import paper_2503_19779_amd as pg
-from gpu_util import Harness, as_f64, same_bits, say
+from gpu_util import Harness, as_f64, same_bits, say, stepwise_check
 from pg_workloads import ChainSpec, KernelSpec, TensorSpec, Ref, EXT, INT, WEIGHT, make_weights, make_inputs
 
 pytestmark = pytest.mark.gpu
@@ -76,13 +79,18 @@ def test_random_chain(seed):
     h = Harness(spec)
     n_seg = spec.kernels[-1].segment + 1
     has_ext = [any(r.kind == EXT for k in spec.kernels if k.segment == s for r in k.ins) for s in range(n_seg)]
-    for t in range(3):
+    done, t = 0, -1
+    while done < 3:
+        t += 1
+        assert t < 12, "too many draws overflow the storage type"
         x_np = make_inputs(spec, t)
-        placed = [place(x, int(rng.choice([0, 0, eb, 2 * eb, 8]))) for x in x_np]
-        ptrs = [p for _, p in placed]
         want = oracle.run_chain(spec, h.w_np, x_np)
         if not all(np.all(np.isfinite(as_f64(want[o]))) for o in spec.outputs):
-            pytest.skip("this draw overflows the storage type")
+            say(f"{spec.name}: iteration {t} overflows the storage type in the oracle; drawing the next one")
+            continue
+        done += 1
+        placed = [place(x, int(rng.choice([0, 0, eb, 2 * eb, 8]))) for x in x_np]
+        ptrs = [p for _, p in placed]
         ref = h.run("eager", ptrs)
         for mode in ("copy", "indirect"):
             h.scrub()
@@ -103,8 +111,11 @@ def test_random_chain(seed):
             gf, of = as_f64(g), as_f64(want[o])
             scale = max(float(np.sqrt(np.mean(of * of))), 1e-30)
             rel_l2 = float(np.sqrt(np.mean((gf - of) ** 2))) / scale
-            worst = float(np.max(np.abs(gf - of) / np.maximum(np.abs(of), scale)))
-            # a chain of up to 14 kernels amplifies single roundings through cancelling adds: aggregate bound tight, elementwise loose
             assert rel_l2 <= (2e-5 if dtype == "f32" else 2e-2), (o, rel_l2)
-            assert worst <= (1e-3 if dtype == "f32" else 0.25), (o, worst)
+        # every kernel on the inputs it actually read: 1e-5 (fp32) / 2e-2 (bf16), element by element
+        h.scrub()
+        worst = stepwise_check(h, x_np, ptrs)
+        for o, b in zip(spec.outputs, ref):
+            assert same_bits(h.chain.output(o), b), ("stepping through", t)
+        say(f"{spec.name}: iteration {t} step by step worst error / tolerance = {worst:.3f}")
     h.close()
