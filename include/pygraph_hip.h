@@ -160,6 +160,33 @@ pg_status pg_eager(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_s
 pg_status pg_eager_range(pg_chain *chain, const void *const *ext_dev_ptrs, int32_t k_begin, int32_t k_end,
                          void *hip_stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace: code that records the
+ * chain into a HIP graph of its own, tight serving loops, harnesses that forbid hipMalloc.  One
+ * eager pass of a chain (as pg_chain_build + pg_eager would run it) whose internal buffers live in a
+ * static device array of PG_STATIC_SCRATCH_BYTES that the library's code object carries -- every GPU
+ * the library runs on holds its own copy until the process ends.  The call allocates and frees no
+ * device memory (no hipMalloc, hipFree, no allocating library routine); its host-side records are
+ * kept from one call to the next and rebuilt only when the descriptor or the weight pointers change.
+ *   kernels .. n_w        [host] the chain, as for pg_chain_build (same rules, same errors).  Only
+ *                         the internal buffers are laid out: no placeholders, no pointer table.
+ *   ext_dev_ptrs [host]   n_ext device pointers [dev], as for pg_eager.
+ *   out_dev [dev]         receives the first out_bytes bytes of internal buffer out_int_index
+ *                         (device-to-device, on the stream, after the last kernel); caller-owned.
+ * Enqueues only; the caller synchronises.  The device the stream belongs to must be current.
+ * Errors: PG_ENOMEM (nothing is launched) if the internal buffers, each aligned to 256 bytes, need
+ * more than PG_STATIC_SCRATCH_BYTES; PG_EINVAL for a malformed descriptor, a bad output index, or
+ * out_bytes beyond that buffer; PG_EHIP if the array's address cannot be resolved or a launch fails.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents; nothing in it
+ * has to start at zero (a pass overwrites every internal buffer before reading it).  Calls that
+ * overlap in time on one GPU -- two streams, two threads -- race on it: serialise them. */
+#define PG_STATIC_SCRATCH_BYTES (4u << 20)
+pg_status pg_eager_static(const pg_kernel_desc *kernels, int32_t n_kernels,
+                          const pg_tensor_desc *ext, int32_t n_ext,
+                          const pg_tensor_desc *ints, int32_t n_int,
+                          const void *const *weight_dev_ptrs, const pg_tensor_desc *weights, int32_t n_w,
+                          const void *const *ext_dev_ptrs,
+                          int32_t out_int_index, void *out_dev, size_t out_bytes, void *hip_stream);
+
 /* One iteration: one launch of the batched copy kernel (external tensors -> placeholders, device
  * to device), then one graph launch per segment (Sec. 4 "Graph-Capture Layer", baseline). */
 pg_status pg_replay_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);

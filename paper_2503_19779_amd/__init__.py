@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     PgError,
     lib,
     select,
+    eager_static,
+    STATIC_SCRATCH_BYTES,
     version,
     EAGER,
     GRAPH_COPY,

@@ -71,6 +71,7 @@ def lib():
         for name in ("pg_eager", "pg_replay_copy", "pg_replay_indirect", "pg_replay_update", "pg_refresh_copy", "pg_refresh_indirect"):
             getattr(L, name).argtypes = [vp, PP, vp]
         L.pg_eager_range.argtypes = [vp, PP, i32, i32, vp]
+        L.pg_eager_static.argtypes = [KP, i32, TP, i32, TP, i32, PP, TP, i32, PP, i32, vp, C.c_size_t, vp]
         L.pg_select.argtypes = [C.POINTER(C.c_double), i32, C.POINTER(C.c_uint8)]
         L.pg_time_kernels.argtypes = [vp, PP, i32, i32, vp, C.POINTER(C.c_float)]
         L.pg_time_refresh_copy.argtypes = [vp, PP, vp, C.POINTER(C.c_float)]
@@ -110,6 +111,21 @@ def select(cost) -> np.ndarray:
     _check(lib().pg_select(cost.ctypes.data_as(C.POINTER(C.c_double)), cost.shape[0],
                            out.ctypes.data_as(C.POINTER(C.c_uint8))))
     return out
+
+
+STATIC_SCRATCH_BYTES = 4 << 20     # PG_STATIC_SCRATCH_BYTES of the header
+
+
+def eager_static(spec, weights: Sequence, ext: Sequence, out_index: int, out, stream) -> None:
+    """pg_eager_static: one eager pass of `spec` with its internal buffers in the library's static device
+    array; the first out.numel() elements of internal buffer out_index land in the caller's tensor `out`."""
+    ks, ext_d, ints_d, w_d = pack_descriptor(spec)
+    wp = _ptr_array(weights, len(spec.weights))
+    xp = _ptr_array(ext, len(spec.ext))
+    s = stream if isinstance(stream, int) else stream.cuda_stream
+    _check(lib().pg_eager_static(ks, len(spec.kernels), ext_d, len(spec.ext), ints_d, len(spec.ints),
+                                 wp, w_d, len(spec.weights), xp, out_index, out.data_ptr(),
+                                 out.numel() * out.element_size(), s))
 
 
 def pack_descriptor(spec):

@@ -18,6 +18,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -119,6 +120,7 @@ struct pg_chain {
     std::vector<CopyList> copy_lists;   // [0] = all externals; then one per segment that has any
     std::vector<std::pair<int, int>> eager_fix;   // (kernel, operand) pairs that take a caller pointer
     bool captured = false;
+    bool eager_only = false;            // built over the static scratch array: pg_eager_static's private chain
     int table_how = PG_TABLE_KERNARG;
     int copy_how = PG_COPY_KERNEL;
     // host-updated graphs: which instance the next replay rewrites, and when each was last launched
@@ -266,16 +268,18 @@ void build_copy_list(CopyList& L, const pg_tensor_desc* ext, const std::vector<s
     }
 }
 
-// Lay out the workspace.  ws may be null (size query).
+// Lay out the workspace.  ws may be null (size query).  eager_only: the chain will never be captured
+// or replayed, so it gets internal buffers only -- no placeholders, pointer table or copy job lists.
 void make_layout(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int n_ext,
-                 const pg_tensor_desc* ints, int n_int, char* ws, Layout& L) {
+                 const pg_tensor_desc* ints, int n_int, char* ws, Layout& L, bool eager_only = false) {
     size_t off = 0;
-    L.ph_off.resize(n_ext);
-    for (int i = 0; i < n_ext; i++) { L.ph_off[i] = off; off = align_up(off + (size_t)ext[i].numel * elem_bytes(ext[i].dtype)); }
+    L.ph_off.assign(n_ext, 0);
+    if (!eager_only)
+        for (int i = 0; i < n_ext; i++) { L.ph_off[i] = off; off = align_up(off + (size_t)ext[i].numel * elem_bytes(ext[i].dtype)); }
     L.int_off.resize(n_int);
     for (int i = 0; i < n_int; i++) { L.int_off[i] = off; off = align_up(off + (size_t)ints[i].numel * elem_bytes(ints[i].dtype)); }
     L.table_off = off;
-    off = align_up(off + (size_t)std::max(1, n_ext) * 8);
+    if (!eager_only) off = align_up(off + (size_t)std::max(1, n_ext) * 8);
     // segments and their external sets
     const int n_seg = k[nk - 1].segment + 1;
     L.seg.assign(n_seg, Segment());
@@ -300,6 +304,7 @@ void make_layout(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int
         L.lists.emplace_back();
         L.lists.back().ext = v;
     }
+    if (eager_only) { L.lists.clear(); L.total = off; return; }
     for (auto& cl : L.lists) {
         build_copy_list(cl, ext, L.ph_off, ws);
         cl.tensors_off = off; off = align_up(off + std::max<size_t>(1, cl.tensors.size()) * sizeof(pgk::CopyTensor));
@@ -313,6 +318,7 @@ const void* operand_ptr(const pg_chain* c, const pg_ref& r, int mode /*0 eager,1
     case PG_REF_WEIGHT: return c->wptr[r.index];
     case PG_REF_INT: return c->ws + c->int_off[r.index];
     case PG_REF_EXT:
+        if (c->eager_only) return nullptr;   // no placeholders, no table: the graph forms are never launched
         if (mode == 1) return c->ws + c->ph_off[r.index];
         if (mode == 2) return c->ws + c->table_off + 8 * (size_t)r.index;
         return nullptr;   // patched per call
@@ -662,6 +668,72 @@ pg_status run_segment(pg_chain* c, int si, int mode, const void* const* ext, hip
     }
 }
 
+// pg_chain_build, and (eager_only) the private chain pg_eager_static lays over the static scratch array
+pg_status build_chain(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor_desc* ext, int32_t n_ext,
+                      const pg_tensor_desc* ints, int32_t n_int, const void* const* weight_dev_ptrs,
+                      const pg_tensor_desc* weights, int32_t n_w, void* workspace_dev, size_t workspace_bytes,
+                      bool eager_only, pg_chain** out) {
+    if (!out) return fail(PG_EINVAL, "null out");
+    *out = nullptr;
+    pg_status st = validate(kernels, nk, ext, n_ext, ints, n_int, weights, n_w);
+    if (st) return st;
+    if (n_w && !weight_dev_ptrs) return fail(PG_EINVAL, "null weight pointer array");
+    for (int i = 0; i < n_w; i++) {
+        if (!weight_dev_ptrs[i]) return fail(PG_EINVAL, "weight pointer %d is null", i);
+        if (reinterpret_cast<uintptr_t>(weight_dev_ptrs[i]) & 15u) return fail(PG_EINVAL, "weight pointer %d is not 16-byte aligned", i);
+    }
+    if (!workspace_dev) return fail(PG_EINVAL, "null workspace");
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return fail(PG_EINVAL, "workspace is not 256-byte aligned");
+    pg_chain* c = new (std::nothrow) pg_chain();
+    if (!c) return fail(PG_ENOMEM, "out of host memory");
+    c->eager_only = eager_only;
+    c->k.assign(kernels, kernels + nk);
+    if (n_ext) c->ext.assign(ext, ext + n_ext);
+    c->ints.assign(ints, ints + n_int);
+    if (n_w) { c->w.assign(weights, weights + n_w); c->wptr.assign(weight_dev_ptrs, weight_dev_ptrs + n_w); }
+    c->ws = static_cast<char*>(workspace_dev);
+    c->ws_bytes = workspace_bytes;
+    Layout L;
+    make_layout(c->k.data(), nk, c->ext.data(), n_ext, c->ints.data(), n_int, c->ws, L, eager_only);
+    c->ws_need = L.total;
+    if (workspace_bytes < L.total) {
+        delete c;
+        return eager_only ? fail(PG_ENOMEM, "the chain's internal buffers need %zu bytes, the static scratch array holds %zu", L.total, workspace_bytes)
+                          : fail(PG_ENOMEM, "workspace has %zu bytes, the chain needs %zu", workspace_bytes, L.total);
+    }
+    c->ph_off = std::move(L.ph_off);
+    c->int_off = std::move(L.int_off);
+    c->table_off = L.table_off;
+    c->copy_lists = std::move(L.lists);
+    c->seg = std::move(L.seg);
+    st = make_records(c);
+    if (st) { delete c; return st; }
+    *out = c;
+    return PG_OK;
+}
+
+// ---- pg_eager_static: internal buffers in a static device array ----------------------------------------
+// The array's name is a host-side stand-in, not a device address: host code uses only the address
+// hipGetSymbolAddress returned for the current device (each GPU holds its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[PG_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+    void* ptr = nullptr;                 // this device's copy of `scratch`
+    pg_chain* chain = nullptr;           // the chain last laid over it (host object only)
+    std::vector<unsigned char> key;      // the bytes of the descriptor that chain was built from
+};
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+template <typename T>
+void key_append(std::vector<unsigned char>& key, const T* p, size_t n) {
+    const unsigned char* b = reinterpret_cast<const unsigned char*>(p);
+    const unsigned long long count = n;
+    key.insert(key.end(), reinterpret_cast<const unsigned char*>(&count), reinterpret_cast<const unsigned char*>(&count) + sizeof count);
+    if (n) key.insert(key.end(), b, b + n * sizeof(T));
+}
+
 double now_us() {
     return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
@@ -701,41 +773,7 @@ pg_status pg_chain_build(const pg_kernel_desc* kernels, int32_t nk, const pg_ten
                          const pg_tensor_desc* ints, int32_t n_int, const void* const* weight_dev_ptrs,
                          const pg_tensor_desc* weights, int32_t n_w, void* workspace_dev, size_t workspace_bytes,
                          pg_chain** out) {
-    if (!out) return fail(PG_EINVAL, "null out");
-    *out = nullptr;
-    pg_status st = validate(kernels, nk, ext, n_ext, ints, n_int, weights, n_w);
-    if (st) return st;
-    if (n_w && !weight_dev_ptrs) return fail(PG_EINVAL, "null weight pointer array");
-    for (int i = 0; i < n_w; i++) {
-        if (!weight_dev_ptrs[i]) return fail(PG_EINVAL, "weight pointer %d is null", i);
-        if (reinterpret_cast<uintptr_t>(weight_dev_ptrs[i]) & 15u) return fail(PG_EINVAL, "weight pointer %d is not 16-byte aligned", i);
-    }
-    if (!workspace_dev) return fail(PG_EINVAL, "null workspace");
-    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return fail(PG_EINVAL, "workspace is not 256-byte aligned");
-    pg_chain* c = new (std::nothrow) pg_chain();
-    if (!c) return fail(PG_ENOMEM, "out of host memory");
-    c->k.assign(kernels, kernels + nk);
-    if (n_ext) c->ext.assign(ext, ext + n_ext);
-    c->ints.assign(ints, ints + n_int);
-    if (n_w) { c->w.assign(weights, weights + n_w); c->wptr.assign(weight_dev_ptrs, weight_dev_ptrs + n_w); }
-    c->ws = static_cast<char*>(workspace_dev);
-    c->ws_bytes = workspace_bytes;
-    Layout L;
-    make_layout(c->k.data(), nk, c->ext.data(), n_ext, c->ints.data(), n_int, c->ws, L);
-    c->ws_need = L.total;
-    if (workspace_bytes < L.total) {
-        delete c;
-        return fail(PG_ENOMEM, "workspace has %zu bytes, the chain needs %zu", workspace_bytes, L.total);
-    }
-    c->ph_off = std::move(L.ph_off);
-    c->int_off = std::move(L.int_off);
-    c->table_off = L.table_off;
-    c->copy_lists = std::move(L.lists);
-    c->seg = std::move(L.seg);
-    st = make_records(c);
-    if (st) { delete c; return st; }
-    *out = c;
-    return PG_OK;
+    return build_chain(kernels, nk, ext, n_ext, ints, n_int, weight_dev_ptrs, weights, n_w, workspace_dev, workspace_bytes, false, out);
 }
 
 pg_status pg_capture(pg_chain* c, void* hip_stream) {
@@ -787,6 +825,58 @@ pg_status pg_eager_range(pg_chain* c, const void* const* ext, int32_t k0, int32_
     if (st) return st;
     if (k0 < 0 || k1 < k0 || k1 > (int)c->k.size()) return fail(PG_EINVAL, "bad kernel range [%d, %d)", k0, k1);
     return run_eager_range(c, k0, k1, ext, static_cast<hipStream_t>(hip_stream));
+}
+
+pg_status pg_eager_static(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor_desc* ext, int32_t n_ext,
+                          const pg_tensor_desc* ints, int32_t n_int, const void* const* weight_dev_ptrs,
+                          const pg_tensor_desc* weights, int32_t n_w, const void* const* ext_dev_ptrs,
+                          int32_t out_int_index, void* out_dev, size_t out_bytes, void* hip_stream) {
+    if (!hip_stream) return fail(PG_EINVAL, "the NULL stream cannot be used; pass a created stream");
+    if (!out_dev || out_bytes == 0) return fail(PG_EINVAL, "null or empty output buffer");
+    if (!kernels || nk <= 0 || n_ext < 0 || n_int <= 0 || n_w < 0 || (n_ext && !ext) || !ints || (n_w && (!weights || !weight_dev_ptrs)))
+        return fail(PG_EINVAL, "bad descriptor arrays");
+    int dev = -1;
+    PG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(PG_EINVAL, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticSlot& slot = g_static[dev];
+    if (!slot.ptr) {
+        void* p = nullptr;
+        PG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(PG_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        slot.ptr = p;
+    }
+    std::vector<unsigned char> key;
+    key_append(key, kernels, (size_t)nk);
+    key_append(key, ext, (size_t)n_ext);
+    key_append(key, ints, (size_t)n_int);
+    key_append(key, weights, (size_t)n_w);
+    key_append(key, weight_dev_ptrs, (size_t)n_w);
+    if (!slot.chain || key != slot.key) {
+        // a new chain: the host-side records are rebuilt (no device memory is touched, nothing is allocated on the device)
+        delete slot.chain;
+        slot.chain = nullptr;
+        slot.key.clear();
+        pg_chain* c = nullptr;
+        pg_status st = build_chain(kernels, nk, ext, n_ext, ints, n_int, weight_dev_ptrs, weights, n_w, slot.ptr,
+                                   (size_t)PG_STATIC_SCRATCH_BYTES, true, &c);
+        if (st) return st;
+        slot.chain = c;
+        slot.key = std::move(key);
+    }
+    pg_chain* c = slot.chain;
+    pg_status st = check_call(c, ext_dev_ptrs, hip_stream, false);
+    if (st) return st;
+    if (out_int_index < 0 || out_int_index >= n_int) return fail(PG_EINVAL, "bad output buffer index %d", out_int_index);
+    const size_t have = (size_t)c->ints[out_int_index].numel * elem_bytes(c->ints[out_int_index].dtype);
+    if (out_bytes > have) return fail(PG_EINVAL, "output asks for %zu bytes, internal buffer %d holds %zu", out_bytes, out_int_index, have);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // Nothing in the array has to start at zero: pg_chain_build's rule that every read of an internal
+    // buffer lies inside what an earlier kernel of the same pass wrote holds here too, so whatever the
+    // previous call left behind is overwritten before it can be read.
+    if ((st = run_eager_range(c, 0, nk, ext_dev_ptrs, s))) return st;
+    PG_HIP(hipMemcpyAsync(out_dev, c->ws + c->int_off[out_int_index], out_bytes, hipMemcpyDeviceToDevice, s));
+    return PG_OK;
 }
 
 pg_status pg_refresh_copy(pg_chain* c, const void* const* ext, void* hip_stream) {
