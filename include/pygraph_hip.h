@@ -219,6 +219,18 @@ pg_status pg_select(const double *cost_us, int32_t n_seg, uint8_t *mode_out);
 pg_status pg_profile(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream,
                      int32_t iters, int32_t inner, double *cost_us_out);
 
+/* The same slow-path measurement taken where the segment will run: between iterations of ANOTHER
+ * chain (Sec. 4.3 measures each graph on its own; a server that alternates between the graphs of
+ * several input shapes replays each one behind a different graph, with cold caches and a host that has
+ * been busy with something else).  A sample is `inner` rounds of [one whole iteration of `background`
+ * in background_mode (pg_mode), then the segment in the mode under test], one synchronisation at the
+ * end, per round, minus the same for the background alone; cost_us_out [host] [n_seg][3] receives the
+ * medians over `iters` samples (never below 0; NaN as in pg_profile).  Both chains must have been
+ * captured (the background only if its mode is a graph mode) and are left with stale internal buffers. */
+pg_status pg_profile_in_context(pg_chain *chain, const void *const *ext_dev_ptrs,
+                                pg_chain *background, const void *const *background_ext_dev_ptrs, int32_t background_mode,
+                                void *hip_stream, int32_t iters, int32_t inner, double *cost_us_out);
+
 /* One iteration with a per-segment mode (mode [host], n_segments entries of pg_mode).  A copy-mode
  * segment refreshes the placeholders of the externals it reads; the pointer table is written once
  * per call if any segment is indirect.  PG_EUNAVAIL if a mode does not exist for its segment. */
@@ -229,32 +241,6 @@ pg_status pg_run_selected(pg_chain *chain, const uint8_t *mode, const void *cons
  * graph launches); for measuring the copy kernel and the table write in isolation. */
 pg_status pg_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
 pg_status pg_refresh_indirect(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream);
-
-/* Timed loop for benchmarks: `iters` iterations of one mode (pg_mode, 3 = pg_run_selected with
- * `mode_per_segment`, 4 = pg_replay_update), iteration t using pointer set t % n_sets of ext_sets [host]
- * ([n_sets][n_ext] device pointers), one stream synchronisation at the end; returns mean
- * microseconds per iteration measured on the host clock. */
-pg_status pg_time_loop(pg_chain *chain, int32_t mode, const uint8_t *mode_per_segment,
-                       const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
-                       double *us_per_iter_out);
-
-/* The same loop with a HIP event after every iteration: us_each_out [host] receives `iters`
- * completion-to-completion times in microseconds (for medians and spreads; the events add a marker
- * per iteration to the stream, so their mean is slightly above pg_time_loop's). */
-pg_status pg_time_loop_each(pg_chain *chain, int32_t mode, const uint8_t *mode_per_segment,
-                            const void *const *ext_sets, int32_t n_sets, int32_t iters, void *hip_stream,
-                            float *us_each_out);
-
-/* GPU execution time of each kernel: launches kernels [k_begin, k_end) eagerly (as pg_eager_range
- * does), each with a pair of events that take the kernel's own start and end timestamps,
- * synchronises the stream, and writes k_end - k_begin durations in microseconds to dur_us_out
- * [host].  For roofline figures: time between launches is not included. */
-pg_status pg_time_kernels(pg_chain *chain, const void *const *ext_dev_ptrs, int32_t k_begin, int32_t k_end,
-                          void *hip_stream, float *dur_us_out);
-
-/* GPU execution time of one copy refresh (the batched copy kernel's launches, summed), measured the
- * same way; *dur_us_out [host] in microseconds.  Synchronises the stream. */
-pg_status pg_time_refresh_copy(pg_chain *chain, const void *const *ext_dev_ptrs, void *hip_stream, float *dur_us_out);
 
 /* Accessors.  Host only. */
 pg_status pg_chain_int_buffer(const pg_chain *chain, int32_t int_index, void **dev_ptr_out, size_t *bytes_out);
@@ -269,6 +255,20 @@ pg_status pg_chain_stats(const pg_chain *chain, pg_stats *out);
 pg_status pg_chain_launch_shape(const pg_chain *chain, int32_t kernel, uint32_t *workgroups_out, uint32_t *threads_out);
 pg_status pg_set_table_refresh(pg_chain *chain, int32_t how /* pg_table_refresh */);
 pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */);
+/* Dispatch merging at capture (on by default).  A graph is "one dispatch, the GPU launches the rest"
+ * (Sec. 2.2); on this machine every dependent kernel node still costs about 1.5 us of dispatch, so a
+ * captured graph, which knows the whole chain, plays a run of up to 4 consecutive kernels with ONE
+ * dispatch where it can: add / mul / GELU (bf16; fp32 except GELU) and RMSNorm over rows of 256 x 16
+ * bytes, all element for element over the same n elements (a whole number of 16-byte vectors).  A
+ * lane runs the kernels in order on its 16 bytes with their stand-alone arithmetic and one rounding
+ * each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
+ * results stay bit-identical to eager launches.  A run ends where a kernel reads something an earlier
+ * kernel of the run wrote in any other pattern than element for element.  Eager launches are never
+ * merged.  `on` = 0 captures one node per kernel.  Takes effect at the next pg_capture. */
+pg_status pg_set_dispatch_merge(pg_chain *chain, int32_t on);
+/* Kernel nodes that the graphs of one replay hold with merging on (*merged_out) and off
+ * (*unmerged_out = the number of kernels).  Either output may be NULL.  Host only. */
+pg_status pg_chain_graph_dispatches(const pg_chain *chain, int32_t *merged_out, int32_t *unmerged_out);
 /* Destroys the graphs and host objects.  The caller has synchronised every stream the chain ran on;
  * device memory stays the caller's.  NULL is allowed. */
 void pg_chain_destroy(pg_chain *chain);

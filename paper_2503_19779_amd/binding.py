@@ -76,6 +76,7 @@ def lib():
         L.pg_time_kernels.argtypes = [vp, PP, i32, i32, vp, C.POINTER(C.c_float)]
         L.pg_time_refresh_copy.argtypes = [vp, PP, vp, C.POINTER(C.c_float)]
         L.pg_profile.argtypes = [vp, PP, vp, i32, i32, C.POINTER(C.c_double)]
+        L.pg_profile_in_context.argtypes = [vp, PP, vp, PP, i32, vp, i32, i32, C.POINTER(C.c_double)]
         L.pg_run_selected.argtypes = [vp, C.POINTER(C.c_uint8), PP, vp]
         L.pg_time_loop.argtypes = [vp, i32, C.POINTER(C.c_uint8), PP, i32, i32, vp, C.POINTER(C.c_double)]
         L.pg_time_loop_each.argtypes = [vp, i32, C.POINTER(C.c_uint8), PP, i32, i32, vp, C.POINTER(C.c_float)]
@@ -86,6 +87,8 @@ def lib():
         L.pg_chain_launch_shape.argtypes = [vp, i32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
         L.pg_set_table_refresh.argtypes = [vp, i32]
         L.pg_set_copy_refresh.argtypes = [vp, i32]
+        L.pg_set_dispatch_merge.argtypes = [vp, i32]
+        L.pg_chain_graph_dispatches.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
         L.pg_chain_destroy.argtypes = [vp]
         L.pg_chain_destroy.restype = None
         L.pg_last_error.restype = C.c_char_p
@@ -280,6 +283,16 @@ class Chain:
                                 cost.ctypes.data_as(C.POINTER(C.c_double))))
         return cost
 
+    def profile_in_context(self, ext, background: "Chain", background_ext, background_mode: int, stream,
+                           iters: int = 9, inner: int = 3) -> np.ndarray:
+        """The cost table measured between iterations of another chain (marginal cost of each segment and mode)."""
+        n_seg = self.stats()["n_segments"]
+        cost = np.zeros((n_seg, 3), np.float64)
+        _check(lib().pg_profile_in_context(self._h, self._ext(ext), background._h, background._ext(background_ext),
+                                           background_mode, self._s(stream), iters, inner,
+                                           cost.ctypes.data_as(C.POINTER(C.c_double))))
+        return cost
+
     def time_loop(self, mode: int, ext_sets: Sequence[Sequence], iters: int, stream, modes=None) -> float:
         """Mean microseconds per iteration over `iters` back-to-back iterations of one mode."""
         n_sets = len(ext_sets)
@@ -332,6 +345,16 @@ class Chain:
 
     def set_copy_refresh(self, how: int):
         _check(lib().pg_set_copy_refresh(self._h, how))
+
+    def set_dispatch_merge(self, on: bool):
+        """Takes effect at the next capture()."""
+        _check(lib().pg_set_dispatch_merge(self._h, 1 if on else 0))
+
+    def graph_dispatches(self):
+        """(kernel nodes per replay with dispatch merging, without it)."""
+        a, b = C.c_int32(), C.c_int32()
+        _check(lib().pg_chain_graph_dispatches(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     # -- views into the workspace
     def _view(self, fn, index, dtype: Optional[str]):

@@ -7,7 +7,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(HERE, "csrc", "kernels.hip"), os.path.join(HERE, "csrc", "chain.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "..", "include", "pygraph_hip.h")]
+HEADERS = [os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "..", "include", "pygraph_hip.h"),
+           os.path.join(HERE, "..", "include", "pygraph_hip_bench.h")]
 LIB = os.path.join(HERE, "libpygraph_hip.so")
 STAMP = os.path.join(HERE, "libpygraph_hip.srchash")   # hash of what LIB was built from
 

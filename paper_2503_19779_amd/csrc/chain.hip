@@ -8,6 +8,7 @@
 // kernel nodes are rewritten from the host before each launch (pg_replay_update); those graphs are
 // built node by node, so that the runtime keeps a handle on every node.
 #include "../../include/pygraph_hip.h"
+#include "../../include/pygraph_hip_bench.h"
 #include "kernels.h"
 
 #include <hip/hip_ext.h>
@@ -78,8 +79,19 @@ struct CopyList {                   // one refresh job: a set of external tensor
     long long bytes = 0;
 };
 
+// A run of consecutive kernels of one segment that a captured graph plays with one dispatch
+// (kernels.h, "merged dispatches").  Runs of one kernel are launched as that kernel.
+struct MergeGroup {
+    int k0 = 0, k1 = 0;              // kernels [k0, k1)
+    long long n = 0;                 // elements every kernel of the run produces
+    // per kernel of the run: where its operands come from (a register slot or memory) and which slot keeps its output
+    unsigned char src0[pgk::kMergeMaxPhases] = {}, src1[pgk::kMergeMaxPhases] = {}, dst[pgk::kMergeMaxPhases] = {};
+    pgk::Launch launch;
+};
+
 struct Segment {
     int k0 = 0, k1 = 0;
+    std::vector<MergeGroup> groups;  // cover [k0, k1) in order
     bool has_ext = false;
     int copy_list = -1;             // index into copy_lists
     hipGraph_t g_copy = nullptr, g_ind = nullptr;
@@ -121,6 +133,7 @@ struct pg_chain {
     std::vector<std::pair<int, int>> eager_fix;   // (kernel, operand) pairs that take a caller pointer
     bool captured = false;
     bool eager_only = false;            // built over the static scratch array: pg_eager_static's private chain
+    bool merge = true;                  // captured graphs play runs of small kernels with one dispatch
     int table_how = PG_TABLE_KERNARG;
     int copy_how = PG_COPY_KERNEL;
     // host-updated graphs: which instance the next replay rewrites, and when each was last launched
@@ -249,6 +262,97 @@ pg_status validate(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, i
     return PG_OK;
 }
 
+pgk::Shape shape_of(const pg_kernel_desc& d) {
+    pgk::Shape sh;
+    sh.n = d.n; sh.m = d.m ? d.m : d.n; sh.rows = d.rows; sh.cols = d.cols; sh.inner = d.inner;
+    return sh;
+}
+
+// Split kernels [k0, k1) of a segment into the runs a captured graph plays with one dispatch each.
+// A run grows while the next kernel (a) is a merge candidate of the run's dtype and element count,
+// (b) finds every operand that an earlier kernel of the run produced still in a register slot, read
+// element for element (an operand produced in the run can never be re-read from memory: its store may
+// not have landed), and (c) neither reads with a broadcast period or as an RMSNorm gain a buffer that
+// the run writes, nor writes one that the run reads that way (units of the tensor are played one after
+// the other, so only element-for-element reads see the right version).  Anything else stands alone.
+void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup>& out) {
+    out.clear();
+    auto whole = [&](const pg_kernel_desc& d, int j, long long n) {   // operand j is read element for element over all n
+        if (d.op == PG_ADD || d.op == PG_MUL) return j == 0 || (d.m ? d.m : d.n) == n;
+        return j == 0;                                                  // GELU a, RMSNORM x
+    };
+    int i = k0;
+    while (i < k1) {
+        MergeGroup g;
+        g.k0 = i;
+        long long n = 0;
+        if (!pgk::merge_candidate(k[i].op, k[i].dtype, shape_of(k[i]), &n)) {
+            g.k1 = ++i;
+            out.push_back(g);
+            continue;
+        }
+        g.n = n;
+        int held[pgk::kMergeSlots];                  // internal buffer whose current contents a slot holds, or -1
+        for (int& h : held) h = -1;
+        std::vector<int> written, broadcast_read;    // internal buffers the run has written / read other than element for element
+        int np = 0;
+        while (i < k1 && np < pgk::kMergeMaxPhases) {
+            const pg_kernel_desc& d = k[i];
+            long long ni = 0;
+            if (!pgk::merge_candidate(d.op, d.dtype, shape_of(d), &ni) || ni != n || d.dtype != k[g.k0].dtype) break;
+            const int nin = n_inputs(d.op);
+            unsigned char src[2] = {(unsigned char)pgk::kMergeFromMemory, (unsigned char)pgk::kMergeFromMemory};
+            bool ok = true;
+            std::vector<int> bc_here;
+            for (int j = 0; j < nin && ok; j++) {
+                if (d.in[j].kind != PG_REF_INT) continue;
+                const int buf = d.in[j].index;
+                const bool produced = std::find(written.begin(), written.end(), buf) != written.end();
+                if (whole(d, j, n)) {
+                    if (!produced) continue;                       // from memory: nothing in the run has touched it yet
+                    ok = false;
+                    for (int q = 0; q < pgk::kMergeSlots; q++)
+                        if (held[q] == buf) { src[j] = (unsigned char)q; ok = true; }
+                } else {
+                    if (produced) ok = false;
+                    bc_here.push_back(buf);
+                }
+            }
+            const int ob = d.out.index;
+            if (std::find(broadcast_read.begin(), broadcast_read.end(), ob) != broadcast_read.end() ||
+                std::find(bc_here.begin(), bc_here.end(), ob) != bc_here.end()) ok = false;
+            if (!ok) break;
+            // slot for the output: the one that holds the buffer's old contents, else a free one, else
+            // the one whose buffer the following kernels need last
+            int q_out = -1;
+            for (int q = 0; q < pgk::kMergeSlots; q++) if (held[q] == ob) q_out = q;
+            for (int q = 0; q < pgk::kMergeSlots && q_out < 0; q++) if (held[q] < 0) q_out = q;
+            if (q_out < 0) {
+                int best_next = -1;
+                for (int q = 0; q < pgk::kMergeSlots; q++) {
+                    int next = 1 << 30;                                   // never needed again
+                    for (int t = i + 1; t < k1 && t < i + 1 + pgk::kMergeMaxPhases && next == (1 << 30); t++) {
+                        for (int j = 0; j < n_inputs(k[t].op); j++)
+                            if (k[t].in[j].kind == PG_REF_INT && k[t].in[j].index == held[q]) next = t;
+                        if (k[t].out.index == held[q] && next == (1 << 30)) break;   // overwritten before it is read
+                    }
+                    if (next > best_next) { best_next = next; q_out = q; }
+                }
+            }
+            held[q_out] = ob;
+            g.src0[np] = src[0];
+            g.src1[np] = src[1];
+            g.dst[np] = (unsigned char)q_out;
+            written.push_back(ob);
+            broadcast_read.insert(broadcast_read.end(), bc_here.begin(), bc_here.end());
+            np++;
+            i++;
+        }
+        g.k1 = i;
+        out.push_back(g);
+    }
+}
+
 void build_copy_list(CopyList& L, const pg_tensor_desc* ext, const std::vector<size_t>& ph_off, char* ws) {
     L.tensors.clear(); L.chunks.clear(); L.groups.clear(); L.bytes = 0;
     for (size_t li = 0; li < L.ext.size(); li++) {
@@ -305,6 +409,7 @@ void make_layout(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int
         L.lists.back().ext = v;
     }
     if (eager_only) { L.lists.clear(); L.total = off; return; }
+    for (auto& sg : L.seg) plan_groups(k, sg.k0, sg.k1, sg.groups);
     for (auto& cl : L.lists) {
         build_copy_list(cl, ext, L.ph_off, ws);
         cl.tensors_off = off; off = align_up(off + std::max<size_t>(1, cl.tensors.size()) * sizeof(pgk::CopyTensor));
@@ -355,8 +460,7 @@ pg_status make_records(pg_chain* c) {
                 break;
             }
         }
-        pgk::Shape sh;
-        sh.n = d.n; sh.m = d.m ? d.m : d.n; sh.rows = d.rows; sh.cols = d.cols; sh.inner = d.inner;
+        const pgk::Shape sh = shape_of(d);
         if (!pgk::plan(d.op, d.dtype, 0, sh, &r.direct) || !pgk::plan(d.op, d.dtype, r.ind_mask, sh, &r.indirect))
             return fail(PG_EINVAL, "kernel %d: no device kernel for op %d dtype %d", i, d.op, d.dtype);
         if (r.direct.grid.x != r.indirect.grid.x || r.direct.block.x != r.indirect.block.x)
@@ -364,13 +468,24 @@ pg_status make_records(pg_chain* c) {
         if (d.op == PG_GEMV)
             for (ArgBlock* a : {&r.a_eager, &r.a_copy, &r.a_ind}) a->gemv.row_groups = (int)r.direct.gemm_row_groups;
     }
+    for (auto& sg : c->seg)
+        for (auto& g : sg.groups) {
+            if (g.k1 - g.k0 < 2) continue;
+            g.launch = pgk::Launch();
+            g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype);
+            if (!g.launch.fn) return fail(PG_EINVAL, "kernel %d: no merged kernel for dtype %d", g.k0, c->k[g.k0].dtype);
+            g.launch.arg_bytes = sizeof(pgk::MergedArgs);
+            const long long nvec = g.n / (c->k[g.k0].dtype == PG_F32 ? 4 : 8);
+            g.launch.grid = dim3((unsigned)((nvec + 255) / 256));       // one workgroup per unit of 256 lanes x 16 bytes
+            g.launch.block = dim3(256);
+        }
     return PG_OK;
 }
 
 // ---- launches ----------------------------------------------------------------------------------------
 // The leanest launch the runtime offers: a module function resolved once, the argument block handed
 // over as one packed buffer (no per-launch symbol lookup, no per-argument marshalling).
-inline hipError_t launch(pgk::Launch& L, ArgBlock* a, hipStream_t s) {
+inline hipError_t launch(pgk::Launch& L, void* a, hipStream_t s) {
     if (!L.mod_fn) {
         hipError_t e = hipGetFuncBySymbol(&L.mod_fn, L.fn);
         if (e != hipSuccess) return e;
@@ -566,13 +681,35 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
     hipError_t le = hipSuccess;
     if (kind == kGraphTableMemcpyNode)   // the graph's first node copies the pointers from its instance's pinned staging
         le = hipMemcpyAsync(c->ws + c->table_off, c->alt[0].host[inst], c->ext.size() * 8, hipMemcpyHostToDevice, s);
-    for (int i = sg.k0; i < sg.k1 && le == hipSuccess; i++) {
-        KernelRec& r = c->rec[i];
-        switch (kind) {
-        case kGraphCopy: le = launch(r.direct, &r.a_copy, s); break;
-        case kGraphHostTable: le = launch(r.indirect, &r.a_host[inst], s); break;
-        default: le = launch(r.indirect, &r.a_ind, s); break;
+    auto block_of = [&](KernelRec& r) -> ArgBlock& { return kind == kGraphCopy ? r.a_copy : kind == kGraphHostTable ? r.a_host[inst] : r.a_ind; };
+    for (auto& grp : sg.groups) {
+        if (le != hipSuccess) break;
+        if (!c->merge || grp.k1 - grp.k0 < 2) {
+            for (int i = grp.k0; i < grp.k1 && le == hipSuccess; i++) {
+                KernelRec& r = c->rec[i];
+                le = launch(kind == kGraphCopy ? r.direct : r.indirect, &block_of(r), s);
+            }
+            continue;
         }
+        // one dispatch for the run: the kernels' own operands, in order, in one argument struct
+        pgk::MergedArgs m;
+        memset(&m, 0, sizeof m);
+        m.n = (unsigned)grp.n;
+        for (int i = grp.k0; i < grp.k1; i++, m.n_phase++) {
+            KernelRec& r = c->rec[i];
+            const pg_kernel_desc& d = c->k[i];
+            const ArgBlock& a = block_of(r);
+            pgk::MergePhase& ph = m.ph[m.n_phase];
+            ph.out = const_cast<void*>(a.ptr[0]);
+            ph.in0 = a.ptr[1];
+            ph.in1 = r.n_in > 1 ? a.ptr[2] : nullptr;
+            ph.m = (d.op == PG_ADD || d.op == PG_MUL) ? (unsigned)(d.m ? d.m : d.n) : 0u;
+            ph.eps = d.op == PG_RMSNORM ? d.eps : 0.f;
+            ph.meta = (unsigned)d.op | ((unsigned)grp.src0[m.n_phase] << 8) | ((unsigned)grp.src1[m.n_phase] << 16) | ((unsigned)grp.dst[m.n_phase] << 24);
+            ph.ind = kind == kGraphCopy ? 0u : (unsigned)r.ind_mask;
+        }
+        for (int q = m.n_phase; q < pgk::kMergeMaxPhases; q++) m.ph[q].meta = (unsigned)PG_GELU;   // operands "from slot 0": fetches nothing, never played
+        le = launch(grp.launch, &m, s);
     }
     hipGraph_t g = nullptr;
     hipError_t ee = hipStreamEndCapture(s, &g);   // always end the capture, even after a failed launch
@@ -979,6 +1116,60 @@ pg_status pg_profile(pg_chain* c, const void* const* ext, void* hip_stream, int3
     return PG_OK;
 }
 
+// One whole iteration of a chain in one mode (no per-segment mixture), for the background of pg_profile_in_context.
+static pg_status run_whole(pg_chain* c, int mode, const void* const* ext, void* hip_stream) {
+    switch (mode) {
+    case PG_EAGER: return run_eager_range(c, 0, (int)c->k.size(), ext, static_cast<hipStream_t>(hip_stream));
+    case PG_GRAPH_COPY: return pg_replay_copy(c, ext, hip_stream);
+    case PG_GRAPH_INDIRECT: return pg_replay_indirect(c, ext, hip_stream);
+    default: return fail(PG_EINVAL, "bad background mode %d", mode);
+    }
+}
+
+pg_status pg_profile_in_context(pg_chain* c, const void* const* ext, pg_chain* bg, const void* const* bg_ext, int32_t bg_mode,
+                                void* hip_stream, int32_t iters, int32_t inner, double* cost) {
+    pg_status st = check_call(c, ext, hip_stream, true);
+    if (st) return st;
+    if ((st = check_call(bg, bg_ext, hip_stream, bg_mode != PG_EAGER))) return st;
+    if (iters <= 0 || inner <= 0 || !cost) return fail(PG_EINVAL, "bad iters/inner/cost");
+    if (bg == c) return fail(PG_EINVAL, "the background chain must be another chain");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((st = run_eager_range(c, 0, (int)c->k.size(), ext, s))) return st;   // every internal buffer holds this iteration's data
+    PG_HIP(hipStreamSynchronize(s));
+    std::vector<double> samples(iters);
+    auto median = [&]() {
+        std::sort(samples.begin(), samples.end());
+        return (iters & 1) ? samples[iters / 2] : 0.5 * (samples[iters / 2 - 1] + samples[iters / 2]);
+    };
+    // the background alone: `inner` iterations back to back, then one synchronisation
+    for (int it = -2; it < iters; it++) {
+        const double t0 = now_us();
+        for (int r = 0; r < inner; r++)
+            if ((st = run_whole(bg, bg_mode, bg_ext, hip_stream))) return st;
+        PG_HIP(hipStreamSynchronize(s));
+        if (it >= 0) samples[it] = (now_us() - t0) / inner;
+    }
+    const double base = median();
+    for (int si = 0; si < (int)c->seg.size(); si++) {
+        for (int m = 0; m < 3; m++) {
+            if (m == PG_GRAPH_INDIRECT && !c->seg[si].has_ext) { cost[3 * si + m] = NAN; continue; }
+            for (int it = -2; it < iters; it++) {
+                const double t0 = now_us();
+                for (int r = 0; r < inner; r++) {
+                    if ((st = run_whole(bg, bg_mode, bg_ext, hip_stream))) return st;
+                    IndCtx x;
+                    if ((st = run_segment(c, si, m, ext, s, &x))) return st;
+                    if ((st = ind_end(c, s, x))) return st;
+                }
+                PG_HIP(hipStreamSynchronize(s));
+                if (it >= 0) samples[it] = (now_us() - t0) / inner;
+            }
+            cost[3 * si + m] = std::max(0.0, median() - base);
+        }
+    }
+    return PG_OK;
+}
+
 pg_status pg_time_loop(pg_chain* c, int32_t mode, const uint8_t* mode_per_segment, const void* const* ext_sets, int32_t n_sets,
                        int32_t iters, void* hip_stream, double* us_out) {
     if (!c || !us_out || n_sets <= 0 || iters <= 0) return fail(PG_EINVAL, "bad arguments");
@@ -1167,6 +1358,21 @@ pg_status pg_chain_launch_shape(const pg_chain* c, int32_t kernel, uint32_t* wor
 pg_status pg_set_table_refresh(pg_chain* c, int32_t how) {
     if (!c || how < PG_TABLE_KERNARG || how > PG_TABLE_HOST) return fail(PG_EINVAL, "bad table refresh kind");
     c->table_how = how;
+    return PG_OK;
+}
+
+pg_status pg_set_dispatch_merge(pg_chain* c, int32_t on) {
+    if (!c) return fail(PG_EINVAL, "null chain");
+    c->merge = on != 0;
+    return PG_OK;
+}
+
+pg_status pg_chain_graph_dispatches(const pg_chain* c, int32_t* merged_out, int32_t* unmerged_out) {
+    if (!c) return fail(PG_EINVAL, "null chain");
+    int n = 0;
+    for (const auto& sg : c->seg) n += (int)sg.groups.size();
+    if (merged_out) *merged_out = n;
+    if (unmerged_out) *unmerged_out = (int)c->k.size();
     return PG_OK;
 }
 

@@ -71,6 +71,36 @@ struct TableArgs {
     const void* ptr[kTableMaxPtrs];
 };
 
+// ---- merged dispatches --------------------------------------------------------------------------------
+// A captured graph need not spend one dispatch per kernel.  A run of consecutive kernels of a chain that
+// all work element for element on the same n elements -- add / mul / GELU, and RMSNorm over rows of
+// exactly 256 x 16 bytes -- goes out as ONE dispatch.  The tensor is cut into units of 256 lanes x 16
+// bytes (lane t owns vector t of a unit; an RMSNorm row is one unit), one workgroup per unit.  The lane
+// runs the kernels one after the other, each with its stand-alone arithmetic and its one rounding to
+// the storage type, stores every kernel's output, and hands the stored bits on to the next kernel in
+// registers when that kernel reads the same buffer element for element -- so the run costs one trip
+// to memory, not one per kernel.  Operands that no kernel of the run produces are fetched up front.
+constexpr int kMergeMaxPhases = 4;        // kernels per merged dispatch
+constexpr int kMergeSlots = 3;            // outputs a lane keeps in registers for later kernels of the run
+constexpr unsigned kMergeFromMemory = 255;
+
+struct MergePhase {
+    void* out;
+    const void* in0;        // ADD / MUL / GELU: a; RMSNORM: x
+    const void* in1;        // ADD / MUL: b; RMSNORM: gain
+    unsigned m;             // ADD / MUL: period of b
+    float eps;              // RMSNORM
+    // op | src0 << 8 | src1 << 16 | dst << 24: the kernel (kAdd, kMul, kGelu, kRmsNorm), the register slot
+    // each operand is taken from (or kMergeFromMemory), the slot that keeps the output
+    unsigned meta;
+    unsigned ind;           // bit 0 / 1: in0 / in1 hold the address of a pointer-table slot
+};
+struct MergedArgs {
+    unsigned n;             // elements every kernel of the run produces (a whole number of 16-byte vectors)
+    int n_phase;
+    MergePhase ph[kMergeMaxPhases];   // entries from n_phase on: meta says "operands from slots", nothing is fetched
+};
+
 struct Launch {
     const void* fn = nullptr;        // host-side kernel handle
     hipFunction_t mod_fn = nullptr;  // the same kernel as a module function, resolved on first launch
@@ -90,5 +120,9 @@ struct Shape {
 bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out);
 const void* copy_kernel();
 const void* table_kernel();
+// Can this kernel be part of a merged dispatch?  From op, dtype and shape alone.  On success *n_out is
+// the number of elements it produces (all kernels of a run must agree on it and on the dtype).
+bool merge_candidate(int op, int dtype, const Shape& shape, long long* n_out);
+const void* merged_kernel(int dtype);
 
 }  // namespace pgk

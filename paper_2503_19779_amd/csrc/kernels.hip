@@ -230,14 +230,15 @@ __device__ __forceinline__ float ew_apply(float a, float b) {
 // Each lane owns U vectors of VB bytes, 256 lanes apart; one block also does the n % NV trailing
 // elements.  `o` may alias `a` (in place): a lane reads what it later overwrites.  AL: a (and b,
 // when it is read by vectors) are VB-aligned.
+// `bid`: the index of the block of 256 lanes this call plays (blockIdx.x in the stand-alone kernel).
 template <typename T, int OP, int VB, int U, typename IdxT, bool AL>
-__device__ __forceinline__ void ew_body(const T* a, const T* b, T* o, IdxT n, IdxT m, bool b_vec) {
+__device__ __forceinline__ void ew_body(const T* a, const T* b, T* o, IdxT n, IdxT m, bool b_vec, unsigned bid) {
     using V = Vec<T, VB>;
     constexpr int NV = V::NV, NW = V::NW;
     constexpr bool kBinary = (OP != kGelu);
     constexpr bool kWide = sizeof(T) == 4;
     const IdxT nvec = n / NV;
-    const IdxT base = (IdxT)blockIdx.x * (kBlock * U) + threadIdx.x;
+    const IdxT base = (IdxT)bid * (kBlock * U) + threadIdx.x;
     unsigned wa[U][NW], wb[U][NW], rb[U][NV];
 #pragma unroll
     for (int u = 0; u < U; u++) {
@@ -275,7 +276,7 @@ __device__ __forceinline__ void ew_body(const T* a, const T* b, T* o, IdxT n, Id
         }
     }
     if constexpr (NV > 1) {
-        if (blockIdx.x == nvec / (kBlock * U)) {   // the block that would own vector index nvec
+        if (bid == nvec / (kBlock * U)) {   // the block that would own vector index nvec
             const IdxT i = nvec * NV + threadIdx.x;
             if (threadIdx.x < NV && i < n) {
                 const float fb1 = kBinary ? load_elem(b + (i % m)) : 0.f;
@@ -295,8 +296,8 @@ __global__ __launch_bounds__(kBlock) void k_elementwise(EwArgs p) {
     const IdxT n = (IdxT)p.n, m = (IdxT)p.m;
     const bool b_vec = kBinary && (m % NV) == 0;      // then a vector of b never wraps around the period
     const bool al = aligned_to(a, VB) && (!b_vec || aligned_to(b, VB));
-    if (al) ew_body<T, OP, VB, U, IdxT, true>(a, b, o, n, m, b_vec);
-    else ew_body<T, OP, VB, U, IdxT, false>(a, b, o, n, m, b_vec);
+    if (al) ew_body<T, OP, VB, U, IdxT, true>(a, b, o, n, m, b_vec, blockIdx.x);
+    else ew_body<T, OP, VB, U, IdxT, false>(a, b, o, n, m, b_vec, blockIdx.x);
 }
 
 // ---- per-channel scale + bias + ReLU on [N, C, inner] ---------------------------------------
@@ -440,19 +441,24 @@ __device__ __forceinline__ void rms_body(const T* x, const T* g, T* o, int cols,
     }
 }
 
-template <typename T, int IND, int VPT, bool RAGGED>
-__global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
-    const int cols = p.cols;
-    const size_t row = blockIdx.x;
-    const T* x = static_cast<const T*>(resolve<(IND & 1) != 0>(p.x)) + row * cols;
-    const T* g = static_cast<const T*>(resolve<(IND & 2) != 0>(p.g));
-    T* o = static_cast<T*>(p.out) + row * cols;
-    __shared__ float part[kBlock / 64];
+// one row by one workgroup of 256 lanes; x0 / o0: the first row
+template <typename T, int VPT, bool RAGGED>
+__device__ __forceinline__ void rms_row(const T* x0, const T* g, T* o0, int cols, float eps, size_t row, float* part) {
+    const T* x = x0 + row * cols;
+    T* o = o0 + row * cols;
     // rows of an aligned buffer stay aligned when cols is a multiple of the vector; else check this row
     const bool al = aligned_to(x, 16) && aligned_to(g, 16);
     const bool al_o = aligned_to(o, 16);
-    if (al) rms_body<T, VPT, RAGGED, true>(x, g, o, cols, p.eps, al_o, part);
-    else rms_body<T, VPT, RAGGED, false>(x, g, o, cols, p.eps, al_o, part);
+    if (al) rms_body<T, VPT, RAGGED, true>(x, g, o, cols, eps, al_o, part);
+    else rms_body<T, VPT, RAGGED, false>(x, g, o, cols, eps, al_o, part);
+}
+
+template <typename T, int IND, int VPT, bool RAGGED>
+__global__ __launch_bounds__(kBlock) void k_rmsnorm(RmsArgs p) {
+    const T* x = static_cast<const T*>(resolve<(IND & 1) != 0>(p.x));
+    const T* g = static_cast<const T*>(resolve<(IND & 2) != 0>(p.g));
+    __shared__ float part[kBlock / 64];
+    rms_row<T, VPT, RAGGED>(x, g, static_cast<T*>(p.out), p.cols, p.eps, blockIdx.x, part);
 }
 
 // ---- GEMV ------------------------------------------------------------------------------------------
@@ -976,6 +982,210 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
     else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
+// ---- merged dispatches ------------------------------------------------------------------------------
+// Same arithmetic as the stand-alone kernels, element for element: ew_apply for add / mul / GELU;
+// RMSNorm as rms_body does it for a row of exactly one vector per lane (fused multiply-add sum of
+// squares in element order, wave_sum, the four wave sums added in a fixed order through LDS,
+// 1 / sqrt(mean + eps), (x * scale) * gain); one rounding to the storage type per kernel (pack), and
+// what a later kernel of the run is handed in registers is exactly the stored bits.
+__device__ __forceinline__ const void* resolve_rt(const void* p, int is_slot) {
+    return is_slot ? *reinterpret_cast<const void* const*>(p) : p;
+}
+
+// One workgroup per unit, straight-line: all operand fetches of the run first (unrolled: their registers
+// need static indices; a lane beyond the tensor re-reads the last vector and never stores, so there is
+// no per-lane branch and all fetches are in flight together), then ONE copy of the arithmetic in a loop
+// over the kernels that picks its operands out of the fetched vectors and the register slots with
+// conditional moves.  Code size counts: the kernel runs once per dispatch on a CU whose instruction
+// cache has most likely never seen it, so every 64 bytes on the executed path are a fetch from memory.
+//
+// Workgroup barrier for an exchange through LDS only: waits for this wave's LDS operations, not for its
+// outstanding global stores (which __syncthreads would, at about a microsecond apiece).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Tensor addresses that reach a kernel through a table or a select are generic pointers to the compiler,
+// and generic loads and stores are counted as LDS operations as well (the barrier above would wait for
+// them).  These say "global memory" outright.
+#define PG_GLOBAL __attribute__((address_space(1)))
+template <typename T, bool AL>
+__device__ __forceinline__ void load_vec_global(const T* p, unsigned* w) {
+    if constexpr (AL) {
+        const v4u t = *(const v4u PG_GLOBAL*)(uintptr_t)p;
+        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+    } else if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = ((const unsigned PG_GLOBAL*)(uintptr_t)p)[i];
+    } else {
+        const unsigned short PG_GLOBAL* q = (const unsigned short PG_GLOBAL*)(uintptr_t)p;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (unsigned)q[2 * i] | ((unsigned)q[2 * i + 1] << 16);
+    }
+}
+template <typename T>
+__device__ __forceinline__ unsigned load_raw_global(const T* p) {
+    if constexpr (sizeof(T) == 4) return *(const unsigned PG_GLOBAL*)(uintptr_t)p;
+    else return *(const unsigned short PG_GLOBAL*)(uintptr_t)p;
+}
+__device__ __forceinline__ void store_vec_global(void* p, const unsigned* w) {
+    v4u t;
+    t.x = w[0]; t.y = w[1]; t.z = w[2]; t.w = w[3];
+    *(v4u PG_GLOBAL*)(uintptr_t)p = t;
+}
+
+template <typename T, bool AL>
+__device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const* in0, const T* const* in1, float* part) {
+    using V = Vec<T, 16>;
+    constexpr int NV = V::NV;
+    constexpr bool kWide = sizeof(T) == 4;
+    constexpr int P = kMergeMaxPhases;
+    const unsigned tid = threadIdx.x;
+    // the run's table, once, in scalar registers (read inside the loop below it would be indexed memory)
+    T* outs[P];
+    unsigned metas[P];
+    float epss[P];
+#pragma unroll
+    for (int i = 0; i < P; i++) {
+        outs[i] = static_cast<T*>(p.ph[i].out);
+        metas[i] = p.ph[i].meta;
+        epss[i] = p.ph[i].eps;
+    }
+    const unsigned n = p.n, nvec = n / NV;
+    const unsigned v = blockIdx.x * kBlock + tid;
+    const bool act = v < nvec;
+    const unsigned i0 = (act ? v : nvec - 1) * NV;
+    unsigned ld0[P][4], ld1[P][4];
+#pragma unroll
+    for (int i = 0; i < P; i++) {
+        const unsigned mt = metas[i], op = mt & 0xffu;
+        if (((mt >> 8) & 0xffu) == kMergeFromMemory) {
+            load_vec_global<T, AL>(in0[i] + i0, ld0[i]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++) ld0[i][k] = 0u;
+        }
+        if (op != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory) {
+            const unsigned m = p.ph[i].m;
+            if (op == kRmsNorm || m % NV == 0) {
+                // RMSNorm: a row is one unit, lane t holds vector t of the gain; add / mul: a vector of b never wraps around the period
+                load_vec_global<T, AL>(in1[i] + (op == kRmsNorm ? tid * NV : (m == n ? i0 : i0 % m)), ld1[i]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; k++) ld1[i][k] = 0u;
+#pragma unroll
+                for (int e = 0; e < NV; e++) {                     // the raw bits, element by element
+                    const unsigned r = load_raw_global(in1[i] + (i0 + e) % m);
+                    if constexpr (sizeof(T) == 4) ld1[i][e] = r;
+                    else ld1[i][e / 2] |= r << (16 * (e & 1));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++) ld1[i][k] = 0u;
+        }
+    }
+    unsigned slot[kMergeSlots][4];
+#pragma unroll
+    for (int q = 0; q < kMergeSlots; q++)
+#pragma unroll
+        for (int k = 0; k < 4; k++) slot[q][k] = 0u;
+    const int n_phase = p.n_phase;
+    // All fetches have been asked for together; wait for them here, once.  Left to the compiler, the wait
+    // sits at the head of the loop below and then also waits, every time round, for the store of the
+    // kernel before (loads and stores of a wave share one counter): a microsecond per kernel.
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+#pragma unroll 1
+    for (int i = 0; i < n_phase; i++) {
+        // this kernel's entry of the table and its fetched operands: uniform selects, no indexing
+        T* out = outs[0];
+        unsigned mt = metas[0];
+        float eps = epss[0];
+        unsigned wa[4], wb[4], wo[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) { wa[k] = ld0[0][k]; wb[k] = ld1[0][k]; }
+#pragma unroll
+        for (int j = 1; j < P; j++)
+            if (i == j) {
+                out = outs[j]; mt = metas[j]; eps = epss[j];
+#pragma unroll
+                for (int k = 0; k < 4; k++) { wa[k] = ld0[j][k]; wb[k] = ld1[j][k]; }
+            }
+        const unsigned op = mt & 0xffu, src0 = (mt >> 8) & 0xffu, src1 = (mt >> 16) & 0xffu, dst = mt >> 24;
+#pragma unroll
+        for (int q = 0; q < kMergeSlots; q++) {
+            if (src0 == (unsigned)q)
+#pragma unroll
+                for (int k = 0; k < 4; k++) wa[k] = slot[q][k];
+            if (src1 == (unsigned)q)
+#pragma unroll
+                for (int k = 0; k < 4; k++) wb[k] = slot[q][k];
+        }
+        float fa[NV], fb[NV], fo[NV];
+        V::unpack(wa, fa);
+        V::unpack(wb, fb);
+        if (op == kRmsNorm) {
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fa[e], fa[e], acc);
+            acc = wave_sum(acc);
+            if ((tid & 63) == 0) part[tid >> 6] = acc;
+            lds_barrier();
+            const float total = ((part[0] + part[1]) + part[2]) + part[3];
+            lds_barrier();                                         // `part` is free for a later RMSNorm of the run
+            const float scale = 1.0f / sqrtf(total / (float)(kBlock * NV) + eps);
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = (fa[e] * scale) * fb[e];
+        } else if (op == kAdd) {
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = ew_apply<kAdd, kWide>(fa[e], fb[e]);
+        } else if (op == kMul) {
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = ew_apply<kMul, kWide>(fa[e], fb[e]);
+        } else {
+            if constexpr (!kWide) {                                // fp32 GELU (evaluated in fp64) is never merged
+#pragma unroll
+                for (int e = 0; e < NV; e++) fo[e] = ew_apply<kGelu, false>(fa[e], 0.f);
+            } else {
+#pragma unroll
+                for (int e = 0; e < NV; e++) fo[e] = fa[e];
+            }
+        }
+        V::pack(fo, wo);
+        if (act) store_vec_global(out + i0, wo);
+#pragma unroll
+        for (int q = 0; q < kMergeSlots; q++)
+            if (dst == (unsigned)q)
+#pragma unroll
+                for (int k = 0; k < 4; k++) slot[q][k] = wo[k];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
+    constexpr int P = kMergeMaxPhases;
+    __shared__ float part[kBlock / 64];
+    // operand addresses, once, before any store of this kernel: pointer-table slots are read with scalar loads
+    const T* in0[P];
+    const T* in1[P];
+    bool al = true;
+#pragma unroll
+    for (int i = 0; i < P; i++) {
+        in0[i] = in1[i] = nullptr;
+        const unsigned mt = p.ph[i].meta;
+        if (((mt >> 8) & 0xffu) == kMergeFromMemory) {
+            in0[i] = static_cast<const T*>(resolve_rt(p.ph[i].in0, p.ph[i].ind & 1));
+            al = al && aligned_to(in0[i], 16);
+        }
+        if ((mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory) {
+            in1[i] = static_cast<const T*>(resolve_rt(p.ph[i].in1, p.ph[i].ind & 2));
+            al = al && aligned_to(in1[i], 16);
+        }
+    }
+    if (al) merged_body<T, true>(p, in0, in1, part);
+    else merged_body<T, false>(p, in0, in1, part);
+}
+
 // ---- batched multi-tensor copy -----------------------------------------------------------------
 // One workgroup per chunk (<= kCopyChunkBytes of one tensor): every lane issues its two 128-bit
 // non-temporal loads, then its two stores, and the workgroup is done -- measured on the log-uniform
@@ -1292,6 +1502,31 @@ bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out) {
     if (dtype == kBF16) return plan_t<bf16_t>(op, ind_mask, shape, out);
     return false;
 }
+bool merge_candidate(int op, int dtype, const Shape& s, long long* n_out) {
+    if (dtype != kF32 && dtype != kBF16) return false;
+    const int nv = dtype == kF32 ? 4 : 8;
+    long long n = 0;
+    if (op == kAdd || op == kMul || op == kGelu) {
+        if (op == kGelu && dtype == kF32) return false;   // evaluated in fp64: too slow on one workgroup to be worth merging
+        if (s.m <= 0) return false;
+        n = s.n;
+    } else if (op == kRmsNorm) {
+        if (s.cols != (long long)kBlock * nv) return false;   // a row must be exactly one unit
+        n = s.rows * s.cols;
+    } else {
+        return false;
+    }
+    if (n <= 0 || n % nv != 0 || n > (1ll << 31)) return false;
+    *n_out = n;
+    return true;
+}
+
+const void* merged_kernel(int dtype) {
+    if (dtype == kF32) return reinterpret_cast<const void*>(&k_merged<float>);
+    if (dtype == kBF16) return reinterpret_cast<const void*>(&k_merged<bf16_t>);
+    return nullptr;
+}
+
 const void* copy_kernel() { return reinterpret_cast<const void*>(&k_copy); }
 const void* table_kernel() { return reinterpret_cast<const void*>(&k_table_write); }
 

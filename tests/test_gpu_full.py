@@ -158,6 +158,7 @@ def test_config5_buckets():
         got = h.chain.output(0).reshape(B, -1)[rows].reshape(-1)
         r = assert_close(got, want, "bf16", f"bucket {B} first 48 kernels")
         say(f"config 5 bucket B={B}: rows {rows} step by step worst {worst:.3f}, 48-kernel prefix worst {r:.3f}")
+    # forced mixtures over a random bucket sequence: every mode of every bucket, interleaved with the others
     seq = bucket_sequence(len(hs), 40)
     sel = [np.zeros(1, np.uint8) + (i % 3) for i in range(len(hs))]
     for it, b in enumerate(seq.tolist()):
@@ -166,6 +167,49 @@ def test_config5_buckets():
         ref = h.run("eager", x_dev)[0]
         got = h.run("selected", x_dev, modes=(sel[b] + it) % 3)[0]
         assert same_bits(got, ref), (it, b)
+    # the selection as the cost model makes it: per bucket, slow-path profile taken between replays of another
+    # bucket's chain -> pg_select -> pg_run_selected over the sequence, bit-equal to eager on every iteration
+    chosen = []
+    for i, h in enumerate(hs):
+        j = (i + 1) % len(hs)
+        _, xi = h.inputs(2000 + i)
+        _, xj = hs[j].inputs(3000 + i)
+        cost = h.chain.profile_in_context(xi, hs[j].chain, xj, pg.GRAPH_INDIRECT, h.stream, iters=5, inner=2)
+        assert cost.shape == (1, 3) and np.all(np.isfinite(cost)) and np.all(cost >= 0)
+        chosen.append(pg.select(cost))
+        assert chosen[-1][0] == int(np.argmin(cost[0])), (cost, chosen[-1])        # deterministic for the table: first minimum
+        assert np.array_equal(pg.select(cost), chosen[-1])
+    say(f"config 5: modes selected per bucket from in-context cost tables: {[int(c[0]) for c in chosen]}")
+    for it, b in enumerate(seq.tolist()):
+        h = hs[b]
+        x_np, x_dev = h.inputs(4000 + it)
+        ref = h.run("eager", x_dev)[0]
+        h.scrub()
+        assert same_bits(h.run("selected", x_dev, modes=chosen[b])[0], ref), (it, b)
+    # timing, with a wide margin: the selected mixture over the sequence is not slower than the best single mode
+    import time
+    stream = hs[0].stream
+    xs = [h.inputs(5000)[1] for h in hs]
+    long_seq = bucket_sequence(len(hs), 200).tolist()
+
+    def run_seq(call):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b in long_seq:
+            call(hs[b], b)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / len(long_seq) * 1e6
+
+    for h in hs:
+        h.stream = stream          # one stream for the whole sequence
+    t = {}
+    for rep in range(2):           # the first round warms up
+        t["eager"] = run_seq(lambda h, b: h.chain.eager(xs[b], stream))
+        t["copy"] = run_seq(lambda h, b: h.chain.replay_copy(xs[b], stream))
+        t["indirect"] = run_seq(lambda h, b: h.chain.replay_indirect(xs[b], stream))
+        t["selected"] = run_seq(lambda h, b: h.chain.run_selected(chosen[b], xs[b], stream))
+    say(f"config 5: us per iteration over a 200-iteration bucket sequence: {t}")
+    assert t["selected"] <= 1.15 * min(t["eager"], t["copy"], t["indirect"]), t
     for h in hs:
         h.close()
 

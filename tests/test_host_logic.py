@@ -21,9 +21,12 @@ from pg_workloads import (ChainSpec, KernelSpec, TensorSpec, Ref, EXT, INT, WEIG
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "pygraph_hip.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(pg_[a-z_]+)\s*\(", hdr))
+    names = set()
+    for h in ("pygraph_hip.h", "pygraph_hip_bench.h"):
+        hdr = open(os.path.join(ROOT, "include", h)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+        names |= set(re.findall(r"\b(pg_[a-z_]+)\s*\(", hdr))
+    assert {"pg_time_loop", "pg_eager_static", "pg_set_dispatch_merge", "pg_profile_in_context"} <= names
     assert {"pg_chain_build", "pg_capture", "pg_replay_copy", "pg_replay_indirect", "pg_select", "pg_eager"} <= names
     L = pg.lib()
     for n in sorted(names):
