@@ -83,8 +83,16 @@ def model_cost(spec, c) -> np.ndarray:
     return out
 
 
-def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile_iters=10):
+def profiler_attached() -> bool:
+    """True under rocprofv3 (it preloads its tool library and announces it in the environment)."""
+    import os
+    keys = ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "HSA_TOOLS_LIB", "ROCPROFILER_LIBRARY_CTOR")
+    return any("rocprof" in os.environ.get(k, "").lower() for k in keys) or "ROCPROF_OUTPUT_PATH" in os.environ
+
+
+def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile_iters=10, merge=True):
     chain = pg.Chain(spec, w_dev)
+    chain.set_dispatch_merge(merge)       # off: one graph node per kernel
     t0 = time.time()
     chain.capture(stream)
     cap_ms = (time.time() - t0) * 1e3
@@ -96,6 +104,13 @@ def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile
                               ("graph_indirect", pg.GRAPH_INDIRECT, None), ("selected", pg.SELECTED, sel)):
         chain.time_loop(mode, sets, warmup, stream, modes)
         us[name] = chain.time_loop(mode, sets, iters, stream, modes)
+    st = chain.stats()
+    if profiler_attached():
+        # the legs below build and destroy further graphs; two counter-collection runs that included them did not complete
+        return chain, {"us_per_iteration": us, "capture_ms": cap_ms,
+                       "cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()],
+                       "selected_mode": sel.tolist(), "kernels": st["n_kernels"], "segments": st["n_segments"],
+                       "launches_per_s": {m: st["n_kernels"] / v * 1e6 for m, v in us.items()}}
     # the two baselines the refresh designs are measured against: host-side rewrite of the kernel
     # nodes' arguments, and the copy refresh as one device-to-device memcpy per tensor
     chain.time_loop(pg.GRAPH_UPDATE, sets, warmup, stream)
@@ -116,6 +131,7 @@ def time_chain(pg, torch, spec, w_dev, make_sets, iters, warmup, stream, profile
     return chain, {"us_per_iteration": us, "capture_ms": cap_ms,
                    "cost_table_us": [[None if not np.isfinite(v) else float(v) for v in row] for row in cost.tolist()],
                    "selected_mode": sel.tolist(), "kernels": st["n_kernels"], "segments": st["n_segments"],
+                   "graph_nodes": chain.graph_dispatches()[0] if merge else st["n_kernels"],
                    "bytes_refreshed_per_replay": {"graph_copy": st["copy_bytes_per_replay"], "graph_indirect": st["table_bytes_per_replay"]},
                    "launches_per_s": {m: st["n_kernels"] / v * 1e6 for m, v in us.items()}}
 
@@ -257,7 +273,7 @@ def main() -> int:
             # launch floor: 512 dependent kernels on 64 elements each, so the time per kernel is the
             # cost of dispatching one dependent kernel (host launch for eager, graph node for replay)
             spec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
-            chain, r = time_chain(pg, torch, spec, [], host_sets(spec, 3), args.iters, 10, stream)
+            chain, r = time_chain(pg, torch, spec, [], host_sets(spec, 3), args.iters, 10, stream, merge=False)
             r["us_per_kernel"] = {m: v / len(spec.kernels) for m, v in r["us_per_iteration"].items()}
         elif cfg == 1:
             spec = elementwise_chain()

@@ -145,8 +145,8 @@ pg_status pg_chain_build(const pg_kernel_desc *kernels, int32_t n_kernels,
  * its kernels on `hip_stream` twice -- once reading the static placeholders, once reading the
  * pointer table -- instantiate and upload the graphs, and write the static part of the copy
  * kernel's job list into the workspace.  Synchronises the stream before returning.  Calling it
- * again re-captures: it first waits for `hip_stream` (replays issued on another stream must have
- * been waited for by the caller) and destroys the old graphs. */
+ * again re-captures: it first waits for everything queued on the device (a replay of the old graphs
+ * may be running on any stream) and destroys the old graphs. */
 pg_status pg_capture(pg_chain *chain, void *hip_stream);
 
 /* One iteration, kernel by kernel from the host with the caller's pointers (the no-graph
@@ -263,14 +263,20 @@ pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */
  * lane runs the kernels in order on its 16 bytes with their stand-alone arithmetic and one rounding
  * each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
  * results stay bit-identical to eager launches.  A run ends where a kernel reads something an earlier
- * kernel of the run wrote in any other pattern than element for element.  Eager launches are never
- * merged.  `on` = 0 captures one node per kernel.  Takes effect at the next pg_capture. */
+ * kernel of the run wrote in any other pattern than element for element.  Likewise up to 3 elementwise
+ * kernels over the outputs of a bf16 GEMV with up to 4 rows of h (GELU of the result, the residual add,
+ * an input add) ride in the GEMV's dispatch as an epilogue: each lane that holds a finished output
+ * rounds it as the GEMV's store would and runs the following kernels on that element.  Outputs that a
+ * later kernel of the same run overwrites are not stored (nothing could read them in between).  Eager
+ * launches are never merged.  `on` = 0 captures one node per kernel.  Takes effect at the next
+ * pg_capture. */
 pg_status pg_set_dispatch_merge(pg_chain *chain, int32_t on);
 /* Kernel nodes that the graphs of one replay hold with merging on (*merged_out) and off
  * (*unmerged_out = the number of kernels).  Either output may be NULL.  Host only. */
 pg_status pg_chain_graph_dispatches(const pg_chain *chain, int32_t *merged_out, int32_t *unmerged_out);
-/* Destroys the graphs and host objects.  The caller has synchronised every stream the chain ran on;
- * device memory stays the caller's.  NULL is allowed. */
+/* Destroys the graphs and host objects, after waiting for everything queued on the device the chain
+ * was captured on (a graph still running, or a copy node still reading pinned staging, must not lose
+ * them).  Device memory stays the caller's.  NULL is allowed. */
 void pg_chain_destroy(pg_chain *chain);
 
 const char *pg_last_error(void);

@@ -83,9 +83,13 @@ struct CopyList {                   // one refresh job: a set of external tensor
 // (kernels.h, "merged dispatches").  Runs of one kernel are launched as that kernel.
 struct MergeGroup {
     int k0 = 0, k1 = 0;              // kernels [k0, k1)
+    bool head = false;               // kernel k0 is a GEMV and the others ride in its dispatch as an epilogue
     long long n = 0;                 // elements every kernel of the run produces
-    // per kernel of the run: where its operands come from (a register slot or memory) and which slot keeps its output
-    unsigned char src0[pgk::kMergeMaxPhases] = {}, src1[pgk::kMergeMaxPhases] = {}, dst[pgk::kMergeMaxPhases] = {};
+    // per kernel of the run: where its operands come from (a register slot or memory), which slot keeps its
+    // output, and whether the output is stored (not if a later kernel of the run overwrites the buffer)
+    static constexpr int kMax = pgk::kMergeMaxPhases > pgk::kEpiMaxPhases + 1 ? pgk::kMergeMaxPhases : pgk::kEpiMaxPhases + 1;
+    unsigned char src0[kMax] = {}, src1[kMax] = {}, dst[kMax] = {};
+    bool store[kMax] = {};
     pgk::Launch launch;
 };
 
@@ -132,6 +136,7 @@ struct pg_chain {
     std::vector<CopyList> copy_lists;   // [0] = all externals; then one per segment that has any
     std::vector<std::pair<int, int>> eager_fix;   // (kernel, operand) pairs that take a caller pointer
     bool captured = false;
+    int device = -1;                    // the device pg_capture ran on (graphs, events and pinned memory belong to it)
     bool eager_only = false;            // built over the static scratch array: pg_eager_static's private chain
     bool merge = true;                  // captured graphs play runs of small kernels with one dispatch
     int table_how = PG_TABLE_KERNARG;
@@ -269,12 +274,16 @@ pgk::Shape shape_of(const pg_kernel_desc& d) {
 }
 
 // Split kernels [k0, k1) of a segment into the runs a captured graph plays with one dispatch each.
-// A run grows while the next kernel (a) is a merge candidate of the run's dtype and element count,
-// (b) finds every operand that an earlier kernel of the run produced still in a register slot, read
-// element for element (an operand produced in the run can never be re-read from memory: its store may
-// not have landed), and (c) neither reads with a broadcast period or as an RMSNorm gain a buffer that
-// the run writes, nor writes one that the run reads that way (units of the tensor are played one after
-// the other, so only element-for-element reads see the right version).  Anything else stands alone.
+// Two kinds of run: a GEMV (the shape k_gemv_shared serves) followed by up to kEpiMaxPhases elementwise
+// kernels over its [rows, n] outputs, which become its epilogue; and up to kMergeMaxPhases
+// element-for-element kernels (add / mul / GELU, RMSNorm over rows of one unit) for one workgroup per unit.
+// A run grows while the next kernel (a) is of the run's dtype and element count, (b) finds every operand
+// that an earlier kernel of the run produced still in a register slot, read element for element (an
+// operand produced in the run can never be re-read from memory: its store may not have landed), and
+// (c) neither reads with a broadcast period or as an RMSNorm gain a buffer that the run writes, nor
+// writes one that the run reads that way, nor (epilogue) writes what the GEMV's other workgroups are
+// still reading -- lanes and workgroups of a run work side by side, so only element-for-element reads
+// see the right version.  Anything else stands alone.
 void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup>& out) {
     out.clear();
     auto whole = [&](const pg_kernel_desc& d, int j, long long n) {   // operand j is read element for element over all n
@@ -286,20 +295,34 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
         MergeGroup g;
         g.k0 = i;
         long long n = 0;
-        if (!pgk::merge_candidate(k[i].op, k[i].dtype, shape_of(k[i]), &n)) {
+        const bool head = pgk::merge_head(k[i].op, k[i].dtype, shape_of(k[i]), &n);
+        if (!head && !pgk::merge_candidate(k[i].op, k[i].dtype, shape_of(k[i]), true, &n)) {
             g.k1 = ++i;
             out.push_back(g);
             continue;
         }
         g.n = n;
+        g.head = head;
         int held[pgk::kMergeSlots];                  // internal buffer whose current contents a slot holds, or -1
         for (int& h : held) h = -1;
         std::vector<int> written, broadcast_read;    // internal buffers the run has written / read other than element for element
         int np = 0;
-        while (i < k1 && np < pgk::kMergeMaxPhases) {
+        int h_buf = -1;                              // (epilogue) the internal buffer the GEMV reads h from
+        const int max_phases = head ? pgk::kEpiMaxPhases + 1 : pgk::kMergeMaxPhases;
+        if (head) {
+            if (k[i].in[1].kind == PG_REF_INT) h_buf = k[i].in[1].index;
+            held[0] = k[i].out.index;
+            g.dst[0] = 0;
+            g.src0[0] = g.src1[0] = (unsigned char)pgk::kMergeFromMemory;
+            written.push_back(k[i].out.index);
+            np = 1;
+            i++;
+        }
+        while (i < k1 && np < max_phases) {
             const pg_kernel_desc& d = k[i];
             long long ni = 0;
-            if (!pgk::merge_candidate(d.op, d.dtype, shape_of(d), &ni) || ni != n || d.dtype != k[g.k0].dtype) break;
+            if (!pgk::merge_candidate(d.op, d.dtype, shape_of(d), !head, &ni) || ni != n || d.dtype != k[g.k0].dtype) break;
+            if (head && d.op == PG_RMSNORM) break;                       // a row-wide reduction cannot ride in a wave's epilogue
             const int nin = n_inputs(d.op);
             unsigned char src[2] = {(unsigned char)pgk::kMergeFromMemory, (unsigned char)pgk::kMergeFromMemory};
             bool ok = true;
@@ -320,7 +343,7 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
             }
             const int ob = d.out.index;
             if (std::find(broadcast_read.begin(), broadcast_read.end(), ob) != broadcast_read.end() ||
-                std::find(bc_here.begin(), bc_here.end(), ob) != bc_here.end()) ok = false;
+                std::find(bc_here.begin(), bc_here.end(), ob) != bc_here.end() || ob == h_buf) ok = false;
             if (!ok) break;
             // slot for the output: the one that holds the buffer's old contents, else a free one, else
             // the one whose buffer the following kernels need last
@@ -331,7 +354,7 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
                 int best_next = -1;
                 for (int q = 0; q < pgk::kMergeSlots; q++) {
                     int next = 1 << 30;                                   // never needed again
-                    for (int t = i + 1; t < k1 && t < i + 1 + pgk::kMergeMaxPhases && next == (1 << 30); t++) {
+                    for (int t = i + 1; t < k1 && t < i + 1 + MergeGroup::kMax && next == (1 << 30); t++) {
                         for (int j = 0; j < n_inputs(k[t].op); j++)
                             if (k[t].in[j].kind == PG_REF_INT && k[t].in[j].index == held[q]) next = t;
                         if (k[t].out.index == held[q] && next == (1 << 30)) break;   // overwritten before it is read
@@ -349,6 +372,13 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
             i++;
         }
         g.k1 = i;
+        // an output is stored unless a later kernel of the run overwrites the same buffer (nothing reads memory in between)
+        for (int a = 0; a < np; a++) {
+            g.store[a] = true;
+            for (int t = a + 1; t < np; t++)
+                if (k[g.k0 + t].out.index == k[g.k0 + a].out.index) g.store[a] = false;
+        }
+        if (head && np == 1) g.head = false;         // no epilogue: the plain GEMV
         out.push_back(g);
     }
 }
@@ -472,12 +502,19 @@ pg_status make_records(pg_chain* c) {
         for (auto& g : sg.groups) {
             if (g.k1 - g.k0 < 2) continue;
             g.launch = pgk::Launch();
-            g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype);
-            if (!g.launch.fn) return fail(PG_EINVAL, "kernel %d: no merged kernel for dtype %d", g.k0, c->k[g.k0].dtype);
-            g.launch.arg_bytes = sizeof(pgk::MergedArgs);
-            const long long nvec = g.n / (c->k[g.k0].dtype == PG_F32 ? 4 : 8);
-            g.launch.grid = dim3((unsigned)((nvec + 255) / 256));       // one workgroup per unit of 256 lanes x 16 bytes
             g.launch.block = dim3(256);
+            if (g.head) {
+                g.launch.fn = pgk::gemv_epilogue_kernel((int)c->k[g.k0].rows);
+                g.launch.arg_bytes = sizeof(pgk::GemvEpiArgs);
+                g.launch.grid = c->rec[g.k0].direct.grid;                   // the GEMV's own launch shape: same workgroups, same lanes
+                if (c->rec[g.k0].direct.block.x != 256) return fail(PG_EINVAL, "kernel %d: unexpected GEMV launch shape", g.k0);
+            } else {
+                g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype);
+                g.launch.arg_bytes = sizeof(pgk::MergedArgs);
+                const long long nvec = g.n / (c->k[g.k0].dtype == PG_F32 ? 4 : 8);
+                g.launch.grid = dim3((unsigned)((nvec + 255) / 256));       // one workgroup per unit of 256 lanes x 16 bytes
+            }
+            if (!g.launch.fn) return fail(PG_EINVAL, "kernel %d: no merged kernel for this run", g.k0);
         }
     return PG_OK;
 }
@@ -568,6 +605,19 @@ pg_status write_table(pg_chain* c, const void* const* ext, hipStream_t s) {
         PG_HIP(hipLaunchKernel(pgk::table_kernel(), dim3(1), dim3(64), args, 0, s));
     }
     return PG_OK;
+}
+
+// Before executable graphs, events or pinned staging go away, nothing on the chain's device may still
+// use them: a replay may have been issued on another stream than the one at hand, and a copy node of a
+// graph reads pinned memory when the graph runs.  Waits for the whole device (graphs are only destroyed
+// on the slow path: re-capture and pg_chain_destroy).
+void quiesce(pg_chain* c) {
+    if (c->device < 0) return;        // never captured: the chain owns no device-side object
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) return;
+    if (cur != c->device && hipSetDevice(c->device) != hipSuccess) return;
+    (void)hipDeviceSynchronize();
+    if (cur != c->device) (void)hipSetDevice(cur);
 }
 
 void destroy_update_graphs(pg_chain* c) {
@@ -689,6 +739,30 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
                 KernelRec& r = c->rec[i];
                 le = launch(kind == kGraphCopy ? r.direct : r.indirect, &block_of(r), s);
             }
+            continue;
+        }
+        if (grp.head) {
+            // the GEMV's dispatch with the following elementwise kernels as its epilogue
+            pgk::GemvEpiArgs e;
+            memset(&e, 0, sizeof e);
+            KernelRec& hr = c->rec[grp.k0];
+            e.g = block_of(hr).gemv;
+            e.head = (kind == kGraphCopy ? 0u : (unsigned)hr.ind_mask) | ((unsigned)grp.dst[0] << 8) | (grp.store[0] ? 1u << 16 : 0u);
+            for (int i = grp.k0 + 1; i < grp.k1; i++, e.n_epi++) {
+                KernelRec& r = c->rec[i];
+                const pg_kernel_desc& d = c->k[i];
+                const ArgBlock& a = block_of(r);
+                const int t = i - grp.k0;
+                pgk::MergePhase& ph = e.ph[e.n_epi];
+                ph.out = const_cast<void*>(a.ptr[0]);
+                ph.in0 = a.ptr[1];
+                ph.in1 = r.n_in > 1 ? a.ptr[2] : nullptr;
+                ph.m = (d.op == PG_ADD || d.op == PG_MUL) ? (unsigned)(d.m ? d.m : d.n) : (unsigned)grp.n;
+                ph.meta = (unsigned)d.op | ((unsigned)grp.src0[t] << 8) | ((unsigned)grp.src1[t] << 16) | ((unsigned)grp.dst[t] << 24);
+                ph.ind = (kind == kGraphCopy ? 0u : (unsigned)r.ind_mask) | (grp.store[t] ? pgk::kEpiStore : 0u);
+            }
+            for (int q = e.n_epi; q < pgk::kEpiMaxPhases; q++) e.ph[q].meta = (unsigned)PG_GELU;   // operands "from slot 0": fetches nothing, never played
+            le = launch(grp.launch, &e, s);
             continue;
         }
         // one dispatch for the run: the kernels' own operands, in order, in one argument struct
@@ -920,7 +994,8 @@ pg_status pg_capture(pg_chain* c, void* hip_stream) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     PG_HIP(hipStreamIsCapturing(s, &cs));
     if (cs != hipStreamCaptureStatusNone) return fail(PG_EINVAL, "the stream is already capturing");
-    if (c->captured) PG_HIP(hipStreamSynchronize(s));   // a replay of the old graphs may still be running on this stream
+    quiesce(c);                       // a replay of the old graphs may still be running, on this stream or another
+    PG_HIP(hipGetDevice(&c->device));
     destroy_graphs(c);
     // static side of the copy kernel's job lists
     for (auto& L : c->copy_lists) {
@@ -1384,6 +1459,7 @@ pg_status pg_set_copy_refresh(pg_chain* c, int32_t how) {
 
 void pg_chain_destroy(pg_chain* c) {
     if (!c) return;
+    quiesce(c);
     destroy_graphs(c);
     for (auto& a : c->alt)
         for (int i = 0; i < 2; i++) {

@@ -101,6 +101,21 @@ struct MergedArgs {
     MergePhase ph[kMergeMaxPhases];   // entries from n_phase on: meta says "operands from slots", nothing is fetched
 };
 
+// The same idea for a GEMV followed by element-for-element kernels over its outputs (GELU of the result,
+// the residual add, an input add): they ride in the GEMV's dispatch as an epilogue.  After the wave's
+// reduction every lane holds the finished sums; lane e of a wave takes output e (row e >> 1 of h, column
+// j0 + (e & 1)), rounds it to the storage type as the GEMV's own store would, and runs the following
+// kernels on that one element, operands fetched while the weights were in flight.  No workgroup needs
+// another's results, so nothing has to be waited for.
+constexpr int kEpiMaxPhases = 3;
+constexpr unsigned kEpiStore = 1u << 8;   // MergePhase::ind: this kernel's output is stored (no later kernel of the run overwrites it)
+struct GemvEpiArgs {
+    GemvArgs g;
+    unsigned head;          // bit 0 / 1: W / h are pointer-table slots; bits 8-15: slot that keeps the GEMV's result; bit 16: store it
+    int n_epi;
+    MergePhase ph[kEpiMaxPhases];   // m: period of in1 (rows * n = element for element)
+};
+
 struct Launch {
     const void* fn = nullptr;        // host-side kernel handle
     hipFunction_t mod_fn = nullptr;  // the same kernel as a module function, resolved on first launch
@@ -122,7 +137,12 @@ const void* copy_kernel();
 const void* table_kernel();
 // Can this kernel be part of a merged dispatch?  From op, dtype and shape alone.  On success *n_out is
 // the number of elements it produces (all kernels of a run must agree on it and on the dtype).
-bool merge_candidate(int op, int dtype, const Shape& shape, long long* n_out);
+// whole_vectors: n must be a whole number of 16-byte vectors (runs of one workgroup per unit; a GEMV's
+// epilogue works element by element and takes any n).
+bool merge_candidate(int op, int dtype, const Shape& shape, bool whole_vectors, long long* n_out);
 const void* merged_kernel(int dtype);
+// Is this the GEMV shape k_gemv_shared<bf16, ., 2, rows> serves (the one the epilogue form exists for)?
+bool merge_head(int op, int dtype, const Shape& shape, long long* n_out);
+const void* gemv_epilogue_kernel(int rows_of_h);
 
 }  // namespace pgk

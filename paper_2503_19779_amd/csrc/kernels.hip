@@ -120,6 +120,44 @@ __device__ __forceinline__ void load_vec(const T* p, unsigned* w) {
     }
 }
 
+// The same fetch through a pointer that says "global memory" outright.  A tensor address that reached the
+// kernel through a pointer-table slot or a run-time choice is a generic pointer to the compiler; generic
+// loads are slower and are counted as LDS operations as well, so a wait for LDS would wait for them too.
+#define PG_GLOBAL __attribute__((address_space(1)))
+#define PG_CONSTANT __attribute__((address_space(4)))
+template <typename T, bool AL, bool NT = false>
+__device__ __forceinline__ void load_vec_global(const T* p, unsigned* w) {
+    if constexpr (AL) {
+        v4u t;
+        if constexpr (NT) t = __builtin_nontemporal_load((const v4u PG_GLOBAL*)(uintptr_t)p);
+        else t = *(const v4u PG_GLOBAL*)(uintptr_t)p;
+        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+    } else if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = ((const unsigned PG_GLOBAL*)(uintptr_t)p)[i];
+    } else {
+        const unsigned short PG_GLOBAL* q = (const unsigned short PG_GLOBAL*)(uintptr_t)p;
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (unsigned)q[2 * i] | ((unsigned)q[2 * i + 1] << 16);
+    }
+}
+template <typename T>
+__device__ __forceinline__ unsigned load_raw_global(const T* p) {
+    if constexpr (sizeof(T) == 4) return *(const unsigned PG_GLOBAL*)(uintptr_t)p;
+    else return *(const unsigned short PG_GLOBAL*)(uintptr_t)p;
+}
+__device__ __forceinline__ void store_vec_global(void* p, const unsigned* w) {
+    v4u t;
+    t.x = w[0]; t.y = w[1]; t.z = w[2]; t.w = w[3];
+    *(v4u PG_GLOBAL*)(uintptr_t)p = t;
+}
+// A pointer-table slot, or the tensor address itself: decided at run time (the merged kernels; the
+// stand-alone ones decide at compile time, resolve<IND>).  The slot is read as constant memory -- nothing
+// writes the table while a graph runs -- which makes it a scalar load that no vector-memory wait covers.
+__device__ __forceinline__ const void* resolve_rt(const void* p, unsigned is_slot) {
+    return is_slot ? *(const void* const PG_CONSTANT*)(uintptr_t)p : p;
+}
+
 // Rows of `cols` elements in 16-byte vectors: nfull = cols / NV full vectors, then (RAGGED shapes
 // only) one partial vector.  Fetching is split in two so that all loads of a kernel can be in flight
 // together: row_vec_issue loads vector min(v, nfull-1) -- always inside the row, no branch -- and
@@ -551,21 +589,34 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
 // over long before the first weight arrives.  Same lanes, same products, same order as gemv_body and
 // gemvb_body: the results are bit-identical.
 static_assert(kBlock == 64 * kGemvChunk, "one vector of h per lane of the workgroup");
-template <typename T, int R, int RB, bool AL>
-__device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */) {
+// `after_issue()` runs once every weight load of the wave has been asked for (the epilogue form of the
+// kernel fetches its own operands there); sums[r][rr] receives the finished dot products, the same bits
+// in every lane.
+// GLOBAL: W and h reached the kernel as generic pointers (through a run-time choice); fetch them with loads
+// that say "global memory" outright.
+template <typename T, int R, int RB, bool AL, bool GLOBAL, class Hook>
+__device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */,
+                                                 Hook after_issue, float (*sums)[RB]) {
     constexpr int NV = Vec<T, 16>::NV;
     constexpr int kCols = 64 * kGemvChunk * NV;
     unsigned hv[RB][4], ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4];
 #pragma unroll
-    for (int rr = 0; rr < RB; rr++) load_vec<T, 16, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
+    for (int rr = 0; rr < RB; rr++) {
+        if constexpr (GLOBAL) load_vec_global<T, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
+        else load_vec<T, 16, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
+    }
     __builtin_amdgcn_sched_barrier(0);   // h first: loads come back in the order they were issued
 #pragma unroll
     for (int r = 0; r < R; r++) {
         const T* wrow = W + (size_t)((j0 + r < n) ? j0 + r : n - 1) * kCols;   // a ragged last group re-reads the last row
 #pragma unroll
-        for (int u = 0; u < kGemvChunk; u++) load_vec<T, 16, AL, true>(wrow + (size_t)(u * 64 + lane) * NV, ww[r][u]);
+        for (int u = 0; u < kGemvChunk; u++) {
+            if constexpr (GLOBAL) load_vec_global<T, AL, true>(wrow + (size_t)(u * 64 + lane) * NV, ww[r][u]);
+            else load_vec<T, 16, AL, true>(wrow + (size_t)(u * 64 + lane) * NV, ww[r][u]);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
+    after_issue();
 #pragma unroll
     for (int rr = 0; rr < RB; rr++) {
         v4u t;
@@ -592,10 +643,18 @@ __device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, i
 #pragma unroll
     for (int rr = 0; rr < RB; rr++)
 #pragma unroll
-        for (int r = 0; r < R; r++) {
-            const float s = wave_sum(acc[r][rr]);
-            if (lane == 0 && j0 + r < n) store_elem(y + (size_t)rr * n + j0 + r, s);
-        }
+        for (int r = 0; r < R; r++) sums[r][rr] = wave_sum(acc[r][rr]);
+}
+
+template <typename T, int R, int RB, bool AL>
+__device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */) {
+    float sums[R][RB];
+    gemv_sums_shared<T, R, RB, AL, false>(W, h, n, j0, lane, tid, hs, [] {}, sums);
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++)
+#pragma unroll
+        for (int r = 0; r < R; r++)
+            if (lane == 0 && j0 + r < n) store_elem(y + (size_t)rr * n + j0 + r, sums[r][rr]);
 }
 
 // RB = rows of h: 1 to 4
@@ -988,10 +1047,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
 // squares in element order, wave_sum, the four wave sums added in a fixed order through LDS,
 // 1 / sqrt(mean + eps), (x * scale) * gain); one rounding to the storage type per kernel (pack), and
 // what a later kernel of the run is handed in registers is exactly the stored bits.
-__device__ __forceinline__ const void* resolve_rt(const void* p, int is_slot) {
-    return is_slot ? *reinterpret_cast<const void* const*>(p) : p;
-}
-
 // One workgroup per unit, straight-line: all operand fetches of the run first (unrolled: their registers
 // need static indices; a lane beyond the tensor re-reads the last vector and never stores, so there is
 // no per-lane branch and all fetches are in flight together), then ONE copy of the arithmetic in a loop
@@ -1003,35 +1058,6 @@ __device__ __forceinline__ const void* resolve_rt(const void* p, int is_slot) {
 // outstanding global stores (which __syncthreads would, at about a microsecond apiece).
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// Tensor addresses that reach a kernel through a table or a select are generic pointers to the compiler,
-// and generic loads and stores are counted as LDS operations as well (the barrier above would wait for
-// them).  These say "global memory" outright.
-#define PG_GLOBAL __attribute__((address_space(1)))
-template <typename T, bool AL>
-__device__ __forceinline__ void load_vec_global(const T* p, unsigned* w) {
-    if constexpr (AL) {
-        const v4u t = *(const v4u PG_GLOBAL*)(uintptr_t)p;
-        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
-    } else if constexpr (sizeof(T) == 4) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = ((const unsigned PG_GLOBAL*)(uintptr_t)p)[i];
-    } else {
-        const unsigned short PG_GLOBAL* q = (const unsigned short PG_GLOBAL*)(uintptr_t)p;
-#pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (unsigned)q[2 * i] | ((unsigned)q[2 * i + 1] << 16);
-    }
-}
-template <typename T>
-__device__ __forceinline__ unsigned load_raw_global(const T* p) {
-    if constexpr (sizeof(T) == 4) return *(const unsigned PG_GLOBAL*)(uintptr_t)p;
-    else return *(const unsigned short PG_GLOBAL*)(uintptr_t)p;
-}
-__device__ __forceinline__ void store_vec_global(void* p, const unsigned* w) {
-    v4u t;
-    t.x = w[0]; t.y = w[1]; t.z = w[2]; t.w = w[3];
-    *(v4u PG_GLOBAL*)(uintptr_t)p = t;
 }
 
 template <typename T, bool AL>
@@ -1184,6 +1210,106 @@ __global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
     }
     if (al) merged_body<T, true>(p, in0, in1, part);
     else merged_body<T, false>(p, in0, in1, part);
+}
+
+// GEMV with an elementwise epilogue: k_gemv_shared's body, then lane e of each wave plays output e through
+// the kernels that follow (see kernels.h).  bf16 only.
+template <int RB>
+__global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
+    constexpr int P = kEpiMaxPhases;
+    // The GEMV's own arguments first, in one batch of scalar loads (see args_up_front): nothing else stands
+    // between the start of the kernel and the weight loads.  The epilogue's table is read once those are on
+    // their way (`fetch`), and kept in scalar registers from then on.
+    args_up_front(p.g);
+    unsigned head = p.head;
+    asm volatile("" : "+s"(head));
+    int n_epi = 0;
+    const void* a0[P];
+    const void* a1[P];
+    bf16_t* outs[P];
+    unsigned ms[P], metas[P], inds[P];
+    const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, head & 1));
+    const bf16_t* h = static_cast<const bf16_t*>(resolve_rt(p.g.h, head & 2));
+    bf16_t* y = static_cast<bf16_t*>(p.g.out);
+    __shared__ v4u hs[RB * kBlock];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = p.g.n;
+    const int j0 = (blockIdx.x * (kBlock / 64) + (tid >> 6)) * 2;
+    const bool mine = lane < 2 * RB && j0 + (lane & 1) < n;
+    const unsigned idx = mine ? (unsigned)(lane >> 1) * (unsigned)n + (unsigned)(j0 + (lane & 1)) : 0u;
+    const unsigned total = (unsigned)RB * (unsigned)n;
+    unsigned ld0[P], ld1[P];
+    // The epilogue's operands: asked for once the weights are on their way (pointer-table slots first, with
+    // scalar loads).  Always the same number of loads -- an operand that comes from a register slot is
+    // fetched from the GEMV's own output buffer instead and ignored -- so that every wait on the weights
+    // knows exactly how many younger loads are outstanding.
+    auto fetch = [&] {
+        // read through the kernel-argument segment's address, made opaque here: otherwise the compiler moves
+        // these loads (invariant memory) back to the top of the kernel, in front of the weight loads
+        const GemvEpiArgs PG_CONSTANT* ka = (const GemvEpiArgs PG_CONSTANT*)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(ka));
+        n_epi = ka->n_epi;
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            a0[i] = ka->ph[i].in0; a1[i] = ka->ph[i].in1; outs[i] = static_cast<bf16_t*>(ka->ph[i].out);
+            ms[i] = ka->ph[i].m; metas[i] = ka->ph[i].meta; inds[i] = ka->ph[i].ind;
+        }
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            const unsigned mt = metas[i];
+            const bool f0 = ((mt >> 8) & 0xffu) == kMergeFromMemory;
+            const bool f1 = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
+            const bf16_t* q0 = f0 ? static_cast<const bf16_t*>(resolve_rt(a0[i], inds[i] & 1)) : y;
+            const bf16_t* q1 = f1 ? static_cast<const bf16_t*>(resolve_rt(a1[i], inds[i] & 2)) : y;
+            const unsigned m = f1 ? ms[i] : total;
+            ld0[i] = load_raw_global(q0 + idx);
+            ld1[i] = load_raw_global(q1 + (m == total ? idx : idx % m));
+        }
+    };
+    float sums[2][RB];
+    if (aligned_to(W, 16) && aligned_to(h, 16)) gemv_sums_shared<bf16_t, 2, RB, true, true>(W, h, n, j0, lane, tid, hs, fetch, sums);
+    else gemv_sums_shared<bf16_t, 2, RB, false, true>(W, h, n, j0, lane, tid, hs, fetch, sums);
+    float v = sums[0][0];
+#pragma unroll
+    for (int rr = 0; rr < RB; rr++)
+#pragma unroll
+        for (int r = 0; r < 2; r++)
+            if (lane == rr * 2 + r) v = sums[r][rr];
+    unsigned bits = f32_to_bf16(v);
+    if (mine && (head & (1u << 16))) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx) = (unsigned short)bits;
+    float slot[kMergeSlots];
+#pragma unroll
+    for (int q = 0; q < kMergeSlots; q++) slot[q] = 0.f;
+    {
+        const unsigned dst = (head >> 8) & 0xffu;
+#pragma unroll
+        for (int q = 0; q < kMergeSlots; q++)
+            if (dst == (unsigned)q) slot[q] = from_raw<bf16_t>(bits);
+    }
+#pragma unroll 1
+    for (int i = 0; i < n_epi; i++) {
+        unsigned mt = metas[0], ind = inds[0], ra = ld0[0], rb = ld1[0];
+        bf16_t* out = outs[0];
+#pragma unroll
+        for (int j = 1; j < P; j++)
+            if (i == j) { mt = metas[j]; ind = inds[j]; ra = ld0[j]; rb = ld1[j]; out = outs[j]; }
+        const unsigned op = mt & 0xffu, src0 = (mt >> 8) & 0xffu, src1 = (mt >> 16) & 0xffu, dst = mt >> 24;
+        float fa = from_raw<bf16_t>(ra), fb = from_raw<bf16_t>(rb);
+#pragma unroll
+        for (int q = 0; q < kMergeSlots; q++) {
+            if (src0 == (unsigned)q) fa = slot[q];
+            if (src1 == (unsigned)q) fb = slot[q];
+        }
+        float fo;
+        if (op == kAdd) fo = ew_apply<kAdd, false>(fa, fb);
+        else if (op == kMul) fo = ew_apply<kMul, false>(fa, fb);
+        else fo = ew_apply<kGelu, false>(fa, 0.f);
+        bits = f32_to_bf16(fo);
+        if (mine && (ind & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(out + idx) = (unsigned short)bits;
+#pragma unroll
+        for (int q = 0; q < kMergeSlots; q++)
+            if (dst == (unsigned)q) slot[q] = from_raw<bf16_t>(bits);
+    }
 }
 
 // ---- batched multi-tensor copy -----------------------------------------------------------------
@@ -1502,7 +1628,7 @@ bool plan(int op, int dtype, int ind_mask, const Shape& shape, Launch* out) {
     if (dtype == kBF16) return plan_t<bf16_t>(op, ind_mask, shape, out);
     return false;
 }
-bool merge_candidate(int op, int dtype, const Shape& s, long long* n_out) {
+bool merge_candidate(int op, int dtype, const Shape& s, bool whole_vectors, long long* n_out) {
     if (dtype != kF32 && dtype != kBF16) return false;
     const int nv = dtype == kF32 ? 4 : 8;
     long long n = 0;
@@ -1516,9 +1642,27 @@ bool merge_candidate(int op, int dtype, const Shape& s, long long* n_out) {
     } else {
         return false;
     }
-    if (n <= 0 || n % nv != 0 || n > (1ll << 31)) return false;
+    if (n <= 0 || (whole_vectors && n % nv != 0) || n > (1ll << 31)) return false;
     *n_out = n;
     return true;
+}
+
+bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
+    // exactly the shapes plan_gemv gives to k_gemv_shared<bf16, IND, 2, rows>
+    if (op != kGemv || dtype != kBF16) return false;
+    if (s.rows < 1 || s.rows > 4 || s.n < 1024 || s.cols != 64 * kGemvChunk * 8) return false;
+    *n_out = s.rows * s.n;
+    return true;
+}
+
+const void* gemv_epilogue_kernel(int rows_of_h) {
+    switch (rows_of_h) {
+    case 1: return reinterpret_cast<const void*>(&k_gemv_epilogue<1>);
+    case 2: return reinterpret_cast<const void*>(&k_gemv_epilogue<2>);
+    case 3: return reinterpret_cast<const void*>(&k_gemv_epilogue<3>);
+    case 4: return reinterpret_cast<const void*>(&k_gemv_epilogue<4>);
+    default: return nullptr;
+    }
 }
 
 const void* merged_kernel(int dtype) {

@@ -29,8 +29,8 @@ def test_merged_graphs_equal_eager_and_unmerged_graphs(batch):
     spec = decode_chain(batch=batch, layers=3, blocks_per_layer=4, hidden=2048, n_ext=6)
     h = Harness(spec, capture=False)
     merged, unmerged = h.chain.graph_dispatches()
-    # the first RMSNorm; then per sub-block the GEMV and one dispatch for GELU, add, (input add,) next RMSNorm
-    assert unmerged == len(spec.kernels) and merged == 1 + 2 * 12, (merged, unmerged)
+    # per sub-block the RMSNorm and one dispatch for the GEMV with GELU, add (and input add) as its epilogue
+    assert unmerged == len(spec.kernels) and merged == 2 * 12, (merged, unmerged)
     h.chain.capture(h.stream)
     x_np, x_dev = h.inputs(0)
     want = h.oracle(x_np)[0]
@@ -46,6 +46,68 @@ def test_merged_graphs_equal_eager_and_unmerged_graphs(batch):
     h.chain.capture(h.stream)
     off = _all_modes(h, x_dev)
     assert same_bits(off["copy"][0], ref) and same_bits(off["indirect"][0], ref)
+    h.close()
+
+
+@pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100)])
+def test_gemv_with_elementwise_epilogue(rows, n):
+    """A GEMV (ragged last workgroup for odd n) followed by GELU in place, an add with an external operand,
+    a mul with a broadcast weight and further kernels: the first three ride in the GEMV's dispatch, the rest
+    form a run of their own.  A second GEMV is followed by a kernel that overwrites the buffer the GEMV reads
+    h from: that one must not ride along."""
+    H = 2048
+    N = rows * n
+    ks = [KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, 0), Ref(EXT, 0)), n, rows=rows, cols=H),      # y
+          KernelSpec("gelu", "bf16", 0, (Ref(INT, 0),), N),                                          # y = gelu(y)
+          KernelSpec("add", "bf16", 1, (Ref(EXT, 1), Ref(INT, 0)), N, m=N),                          # x = e1 + y
+          KernelSpec("mul", "bf16", 1, (Ref(INT, 1), Ref(WEIGHT, 1)), N, m=5),                       # x *= w1[i % 5]
+          KernelSpec("add", "bf16", 2, (Ref(INT, 1), Ref(INT, 0)), N, m=N),                          # z = x + y      (fourth: its own dispatch)
+          KernelSpec("gemv", "bf16", 3, (Ref(WEIGHT, 0), Ref(INT, 4)), n, rows=rows, cols=H),        # needs int 4 = h2, written below first
+          ]
+    # h2 must exist before the second GEMV: produce it first from the external h
+    ks.insert(5, KernelSpec("add", "bf16", 4, (Ref(EXT, 0), Ref(EXT, 0)), rows * H, m=rows * H))     # h2 = 2 * e0
+    ks.append(KernelSpec("mul", "bf16", 3, (Ref(INT, 3), Ref(INT, 2)), N, m=N))                      # epilogue of the second GEMV
+    ks.append(KernelSpec("add", "bf16", 4, (Ref(EXT, 0), Ref(EXT, 0)), rows * H, m=rows * H))        # rewrites h2: other element count, separate anyway
+    spec = ChainSpec(f"gemv_epilogue_{rows}x{n}", ks,
+                     [TensorSpec("bf16", rows * H), TensorSpec("bf16", N)],
+                     [TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", rows * H)],
+                     [TensorSpec("bf16", n * H, ("normal", 0.0, 0.02)), TensorSpec("bf16", 5, ("normal", 1.0, 0.3))], [0, 1, 2, 3, 4], 6006)
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
+    # [gemv gelu add mul] [add] [add] [gemv mul] [add]; the two adds in the middle merge too when they have the same element count
+    assert unmerged == 9 and merged == (4 if n == H else 5), merged
+    h.chain.capture(h.stream)
+    for t in range(4):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        for o in range(5):
+            assert same_bits(outs["eager"][o], outs["copy"][o]) and same_bits(outs["eager"][o], outs["indirect"][o]), (t, o)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
+    h.close()
+
+
+def test_epilogue_never_overwrites_what_the_gemv_is_reading():
+    """A kernel after the GEMV that writes the buffer h comes from has the right shape to ride along only
+    when n == cols; it must still get a dispatch of its own (other workgroups are still reading h)."""
+    H = 2048
+    ks = [KernelSpec("add", "bf16", 0, (Ref(EXT, 0), Ref(EXT, 0)), H, m=H),                  # h = 2 e0
+          KernelSpec("gemv", "bf16", 1, (Ref(WEIGHT, 0), Ref(INT, 0)), H, rows=1, cols=H),   # y = W h
+          KernelSpec("add", "bf16", 0, (Ref(INT, 1), Ref(EXT, 0)), H, m=H),                  # h = y + e0   <- writes h
+          KernelSpec("gelu", "bf16", 1, (Ref(INT, 1),), H)]
+    spec = ChainSpec("epilogue_hazard", ks, [TensorSpec("bf16", H)], [TensorSpec("bf16", H), TensorSpec("bf16", H)],
+                     [TensorSpec("bf16", H * H, ("normal", 0.0, 0.02))], [0, 1], 6007)
+    h = Harness(spec, capture=False)
+    assert h.chain.graph_dispatches() == (3, 4)      # [add] [gemv] [add gelu]
+    h.chain.capture(h.stream)
+    for t in range(3):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        for o in range(2):
+            assert same_bits(outs["eager"][o], outs["copy"][o]) and same_bits(outs["eager"][o], outs["indirect"][o]), (t, o)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
     h.close()
 
 
