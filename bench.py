@@ -129,10 +129,12 @@ def main() -> int:
     dispatches_merged, dispatches_unmerged = chain.graph_dispatches()
 
     # graphs with one node per kernel first (the plain form of a captured graph), then with dispatch merging
-    chain.set_dispatch_merge(False)
-    chain.capture(stream)
-    us_plain = {name: timed(chain, x_dev, mode, K, W) for name, mode in MODES[1:]}
-    log(f"[bench] graphs with one node per kernel ({dispatches_unmerged} nodes): {us_plain}")
+    us_plain = {}
+    if not under_profiler:          # a re-capture destroys graphs: kept out of profiled runs (see --no-refresh-baselines)
+        chain.set_dispatch_merge(False)
+        chain.capture(stream)
+        us_plain = {name: timed(chain, x_dev, mode, K, W) for name, mode in MODES[1:]}
+        log(f"[bench] graphs with one node per kernel ({dispatches_unmerged} nodes): {us_plain}")
     chain.set_dispatch_merge(True)
     t0 = time.time()
     chain.capture(stream)
@@ -175,55 +177,80 @@ def main() -> int:
     # 512 dependent kernels that do next to nothing (64 elements each), one graph node per kernel: the
     # time per node of a replay and the time per launch of the eager loop are what a kernel costs here
     # before it does any work; their ratio is the ceiling of graph over eager for launch-bound chains.
-    fspec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
-    fchain = pg.Chain(fspec, [], dev)
-    fchain.set_dispatch_merge(False)
-    fchain.capture(stream)
-    fx = [[to_device(x, dev) for x in make_inputs(fspec, t)] for t in range(3)]
-    graph_node_us = timed(fchain, fx, pg.GRAPH_INDIRECT, 50, 10) / len(fspec.kernels)
-    eager_launch_us = timed(fchain, fx, pg.EAGER, 50, 10) / len(fspec.kernels)
-    fchain.close()
-    log(f"[bench] dispatch floor: {graph_node_us:.2f} us per graph node, {eager_launch_us:.2f} us per eager launch")
+    # (Not under a profiler: it belongs to the legs whose profiled runs did not complete.)
+    graph_node_us = eager_launch_us = None
+    if not under_profiler:
+        fspec = elementwise_chain(n_kernels=512, numel=64, dtype="bf16")
+        fchain = pg.Chain(fspec, [], dev)
+        fchain.set_dispatch_merge(False)
+        fchain.capture(stream)
+        fx = [[to_device(x, dev) for x in make_inputs(fspec, t)] for t in range(3)]
+        graph_node_us = timed(fchain, fx, pg.GRAPH_INDIRECT, 50, 10) / len(fspec.kernels)
+        eager_launch_us = timed(fchain, fx, pg.EAGER, 50, 10) / len(fspec.kernels)
+        fchain.close()
+        log(f"[bench] dispatch floor: {graph_node_us:.2f} us per graph node, {eager_launch_us:.2f} us per eager launch")
 
-    # ------------------------------------------------------------------ the dominant kernel alone: GEMV 2048x2048, HIP events on the launch stream
-    # A graph of the chain's 120 GEMV launches and nothing else (same kernel, same launch shape, the
-    # chain's own 120 weight matrices, input vector fixed): events around R replays give the time per
-    # launch.  It includes the dispatch gap between two dependent launches, so it is an upper bound of
-    # the kernel's own duration (the rocprofv3 kernel trace gives the latter).
+    # ------------------------------------------------------------------ the dominant kernel alone, HIP events on the launch stream
+    # In graph replay the dominant kernel is the GEMV 2048x2048 with its epilogue (GELU of the result and the
+    # residual add ride in its dispatch); in eager launches it is the plain GEMV.  Each is timed in a graph of
+    # the chain's 120 such launches and nothing else (same kernels, same launch shapes, the chain's own 120
+    # weight matrices, input vector fixed): events around R replays give the time per launch.  It includes
+    # the dispatch gap between two dependent launches, so it is an upper bound of the kernel's own duration
+    # (the rocprofv3 kernel trace gives the latter).
+    from pg_workloads import INT
     n_gemv = sum(1 for k in spec.kernels if k.op == "gemv")
     H = spec.meta["hidden"]
-    gspec = ChainSpec("gemv_only", [KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s), Ref(WEIGHT, n_gemv)), H, rows=1, cols=H) for s in range(n_gemv)],
-                      [], [TensorSpec("bf16", H)], list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H)], [0])
-    gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0]], dev)
-    gchain.capture(stream)
     reps = 50
-    for _ in range(5):
-        gchain.replay_copy([], stream)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(reps):
-        gchain.replay_copy([], stream)        # no external input: this is the graph launch alone
-    e1.record(stream)
-    e1.synchronize()
-    gemv_us = e0.elapsed_time(e1) * 1e3 / (reps * n_gemv)
-    gchain.close()
+
+    def gemv_graph_us(with_epilogue: bool) -> float:
+        ks = []
+        for s_ in range(n_gemv):
+            ks.append(KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s_), Ref(WEIGHT, n_gemv)), H, rows=1, cols=H))
+            if with_epilogue:
+                ks.append(KernelSpec("gelu", "bf16", 0, (Ref(INT, 0),), H))
+                ks.append(KernelSpec("add", "bf16", 1, (Ref(INT, 1) if s_ else Ref(WEIGHT, n_gemv), Ref(INT, 0)), H, m=H))
+        gspec = ChainSpec("gemv_only", ks, [], [TensorSpec("bf16", H), TensorSpec("bf16", H)], list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H)], [0])
+        gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0]], dev)
+        assert gchain.graph_dispatches()[0] == n_gemv
+        gchain.capture(stream)
+        for _ in range(5):
+            gchain.replay_copy([], stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            gchain.replay_copy([], stream)        # no external input: this is the graph launch alone
+        e1.record(stream)
+        e1.synchronize()
+        gchain.close()
+        return e0.elapsed_time(e1) * 1e3 / (reps * n_gemv)
+
+    gemv_us = gemv_graph_us(False)
+    epi_us = gemv_graph_us(True)
     gemv_bytes = H * H * 2 + H * 2 + H * 2       # bf16 weight matrix + input vector + output vector
-    log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s")
+    epi_bytes = H * H * 2 + H * 2 + H * 2 + 2 * H * 2    # + the residual stream read, and the GELU result and the new stream written
+    log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s; with GELU + residual add as its epilogue: {epi_us:.2f} us = {epi_bytes / epi_us / 1e3:.0f} GB/s")
     tr = profile_figures("decode_chain_b1_kernel_trace.md")
     hb = profile_figures("gemv_and_copy_kernel_hbm_traffic.md")
-    roofline = {"kernel": "k_gemv_shared<bf16> 2048x2048, batch 1", "bound": "hbm", "achieved": gemv_bytes / gemv_us / 1e3,
-                "peak": HBM_PEAK, "unit": "GB/s", "frac": gemv_bytes / gemv_us / 1e3 / HBM_PEAK,
-                "frac_denominator": "avg_launch_us: HIP events on the launch stream around 50 replays of a graph of the chain's 120 GEMV launches; "
-                                    "the time per launch includes the dispatch gap between two dependent launches",
-                "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": reps * n_gemv,
+    how = ("HIP events on the launch stream around 50 replays of a graph of the chain's 120 launches of this kernel; "
+           "the time per launch includes the dispatch gap between two dependent launches")
+    roofline = {"kernel": "k_gemv_epilogue<1>: bf16 GEMV 2048x2048, batch 1, with GELU and the residual add as its epilogue (one graph node; the dominant kernel of graph replay)",
+                "bound": "hbm", "achieved": epi_bytes / epi_us / 1e3, "peak": HBM_PEAK, "unit": "GB/s", "frac": epi_bytes / epi_us / 1e3 / HBM_PEAK,
+                "frac_denominator": "avg_launch_us: " + how,
+                "bytes_per_launch": epi_bytes, "avg_launch_us": epi_us, "launches_timed": reps * n_gemv,
                 # the same bytes over the kernel's own duration in the committed rocprofv3 kernel trace (dispatch start to end, mean over all its dispatches)
-                "profile_kernel_mean_us": tr.get("gemv_kernel_mean_us"),
-                "frac_from_profile": (gemv_bytes / tr["gemv_kernel_mean_us"] / 1e3 / HBM_PEAK) if tr.get("gemv_kernel_mean_us") else None,
+                "profile_kernel_mean_us": tr.get("gemv_epilogue_kernel_mean_us"),
+                "frac_from_profile": (epi_bytes / tr["gemv_epilogue_kernel_mean_us"] / 1e3 / HBM_PEAK) if tr.get("gemv_epilogue_kernel_mean_us") else None,
                 "frac_from_profile_source": "profiles/decode_chain_b1_kernel_trace.md (rocprofv3 --kernel-trace --stats)",
                 # HBM bytes per launch from the committed hardware-counter runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain 256 MiB copy)
-                "traffic": hb.get("gemv_traffic_bytes_per_launch"),
+                "traffic": hb.get("gemv_epilogue_traffic_bytes_per_launch"),
                 "traffic_source": "profiles/gemv_and_copy_kernel_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)",
-                "dispatch_floor_us_per_node": graph_node_us}
+                "dispatch_floor_us_per_node": graph_node_us,
+                # the plain GEMV (what an eager launch and a graph with one node per kernel run), measured the same way
+                "gemv_alone": {"kernel": "k_gemv_shared<bf16> 2048x2048, batch 1", "achieved": gemv_bytes / gemv_us / 1e3, "frac": gemv_bytes / gemv_us / 1e3 / HBM_PEAK,
+                               "bytes_per_launch": gemv_bytes, "avg_launch_us": gemv_us, "launches_timed": reps * n_gemv,
+                               "profile_kernel_mean_us": tr.get("gemv_kernel_mean_us"),
+                               "frac_from_profile": (gemv_bytes / tr["gemv_kernel_mean_us"] / 1e3 / HBM_PEAK) if tr.get("gemv_kernel_mean_us") else None,
+                               "traffic": hb.get("gemv_traffic_bytes_per_launch")}}
     chain_bytes = sum(t.nbytes for t in spec.weights)     # every weight is read once per iteration
     chain_level = {m: chain_bytes / us[m] / 1e3 for m in us}
 
