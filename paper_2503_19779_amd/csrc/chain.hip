@@ -48,6 +48,7 @@ pg_status fail(pg_status st, const char* fmt, ...) {
     } while (0)
 
 constexpr size_t kAlign = 256;
+constexpr size_t kNoShadow = ~(size_t)0;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 size_t elem_bytes(int dtype) { return dtype == PG_F32 ? 4 : 2; }
 
@@ -83,11 +84,14 @@ struct CopyList {                   // one refresh job: a set of external tensor
 // (kernels.h, "merged dispatches").  Runs of one kernel are launched as that kernel.
 struct MergeGroup {
     int k0 = 0, k1 = 0;              // kernels [k0, k1)
-    bool head = false;               // kernel k0 is a GEMV and the others ride in its dispatch as an epilogue
+    bool head = false;               // the run is a GEMV's dispatch: the kernels after the GEMV ride in it as an epilogue
+    bool pro = false;                // (head) kernel k0 is the RMSNorm that feeds the GEMV k0 + 1, and rides in front of it as a prologue
+    int rename = -1;                 // (pro) internal buffer the RMSNorm reads and the run overwrites: the run writes its other copy
     long long n = 0;                 // elements every kernel of the run produces
+    int gemv() const { return k0 + (pro ? 1 : 0); }
     // per kernel of the run: where its operands come from (a register slot or memory), which slot keeps its
     // output, and whether the output is stored (not if a later kernel of the run overwrites the buffer)
-    static constexpr int kMax = pgk::kMergeMaxPhases > pgk::kEpiMaxPhases + 1 ? pgk::kMergeMaxPhases : pgk::kEpiMaxPhases + 1;
+    static constexpr int kMax = pgk::kMergeMaxPhases > pgk::kEpiMaxPhases + 2 ? pgk::kMergeMaxPhases : pgk::kEpiMaxPhases + 2;
     unsigned char src0[kMax] = {}, src1[kMax] = {}, dst[kMax] = {};
     bool store[kMax] = {};
     pgk::Launch launch;
@@ -130,6 +134,7 @@ struct pg_chain {
     char* ws = nullptr;
     size_t ws_bytes = 0, ws_need = 0;
     std::vector<size_t> ph_off, int_off;
+    std::vector<size_t> shadow_off;     // per internal buffer: its second copy (merged dispatches that rename), or kNoShadow
     size_t table_off = 0;
     std::vector<KernelRec> rec;
     std::vector<Segment> seg;
@@ -160,7 +165,7 @@ namespace {
 
 // ---- descriptor validation and layout ------------------------------------------------------------
 struct Layout {
-    std::vector<size_t> ph_off, int_off;
+    std::vector<size_t> ph_off, int_off, shadow_off;
     size_t table_off = 0;
     std::vector<CopyList> lists;
     std::vector<Segment> seg;
@@ -275,7 +280,8 @@ pgk::Shape shape_of(const pg_kernel_desc& d) {
 
 // Split kernels [k0, k1) of a segment into the runs a captured graph plays with one dispatch each.
 // Two kinds of run: a GEMV (the shape k_gemv_shared serves) followed by up to kEpiMaxPhases elementwise
-// kernels over its [rows, n] outputs, which become its epilogue; and up to kMergeMaxPhases
+// kernels over its [rows, n] outputs, which become its epilogue -- and preceded, if the kernel before it
+// is the RMSNorm that produces its input, by that RMSNorm as a prologue; and up to kMergeMaxPhases
 // element-for-element kernels (add / mul / GELU, RMSNorm over rows of one unit) for one workgroup per unit.
 // A run grows while the next kernel (a) is of the run's dtype and element count, (b) finds every operand
 // that an earlier kernel of the run produced still in a register slot, read element for element (an
@@ -284,7 +290,14 @@ pgk::Shape shape_of(const pg_kernel_desc& d) {
 // writes one that the run reads that way, nor (epilogue) writes what the GEMV's other workgroups are
 // still reading -- lanes and workgroups of a run work side by side, so only element-for-element reads
 // see the right version.  Anything else stands alone.
-void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup>& out) {
+//
+// One exception to (c): every workgroup of a run with a prologue reads all of the RMSNorm's input x,
+// and the epilogue may overwrite that very buffer (the residual add of a decoder block does).  Such a run
+// renames: it writes the buffer's second copy in the workspace, and the kernels that follow use that copy
+// (capture_segment keeps track) -- allowed when the run rewrites the whole buffer.  At the end of a
+// segment every buffer must be back in its first copy, where the other modes and the caller look for it:
+// a buffer renamed an odd number of times has its last renaming run split back into RMSNorm + GEMV run.
+void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* ints, std::vector<MergeGroup>& out) {
     out.clear();
     auto whole = [&](const pg_kernel_desc& d, int j, long long n) {   // operand j is read element for element over all n
         if (d.op == PG_ADD || d.op == PG_MUL) return j == 0 || (d.m ? d.m : d.n) == n;
@@ -295,27 +308,56 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
         MergeGroup g;
         g.k0 = i;
         long long n = 0;
-        const bool head = pgk::merge_head(k[i].op, k[i].dtype, shape_of(k[i]), &n);
+        // RMSNorm [rows, 2048] straight into a GEMV of the epilogue kernel's shape?
+        bool pro = false;
+        if (k[i].op == PG_RMSNORM && k[i].dtype == PG_BF16 && i + 1 < k1 && k[i].rows >= 1 && k[i].rows <= 4) {
+            const pg_kernel_desc& v = k[i + 1];
+            long long nv = 0;
+            pro = pgk::merge_head(v.op, v.dtype, shape_of(v), &nv) && k[i].cols == v.cols && k[i].rows == v.rows &&
+                  v.in[1].kind == PG_REF_INT && v.in[1].index == k[i].out.index &&
+                  !(v.in[0].kind == PG_REF_INT && v.in[0].index == k[i].out.index);
+            if (pro) {
+                // the GEMV itself may overwrite x: renamed like an epilogue kernel's write, if it covers the buffer
+                const pg_ref& x = k[i].in[0];
+                if (x.kind == PG_REF_INT && v.out.index == x.index && ints[x.index].numel != nv) pro = false;
+            }
+        }
+        const int hk = i + (pro ? 1 : 0);
+        const bool head = pro || pgk::merge_head(k[i].op, k[i].dtype, shape_of(k[i]), &n);
         if (!head && !pgk::merge_candidate(k[i].op, k[i].dtype, shape_of(k[i]), true, &n)) {
             g.k1 = ++i;
             out.push_back(g);
             continue;
         }
+        if (pro) pgk::merge_head(k[hk].op, k[hk].dtype, shape_of(k[hk]), &n);
         g.n = n;
         g.head = head;
+        g.pro = pro;
         int held[pgk::kMergeSlots];                  // internal buffer whose current contents a slot holds, or -1
         for (int& h : held) h = -1;
         std::vector<int> written, broadcast_read;    // internal buffers the run has written / read other than element for element
         int np = 0;
         int h_buf = -1;                              // (epilogue) the internal buffer the GEMV reads h from
-        const int max_phases = head ? pgk::kEpiMaxPhases + 1 : pgk::kMergeMaxPhases;
+        int x_buf = -1;                              // (prologue) the internal buffer the RMSNorm reads
+        const int max_phases = head ? pgk::kEpiMaxPhases + 1 + (pro ? 1 : 0) : pgk::kMergeMaxPhases;
         if (head) {
+            if (pro) {
+                if (k[i].in[0].kind == PG_REF_INT) x_buf = k[i].in[0].index;
+                if (k[i].in[1].kind == PG_REF_INT) broadcast_read.push_back(k[i].in[1].index);   // the gain
+                written.push_back(k[i].out.index);   // stored by one workgroup, held in no slot: the run cannot read it back
+                g.src0[0] = g.src1[0] = (unsigned char)pgk::kMergeFromMemory;
+                g.store[0] = true;
+                np = 1;
+                i++;
+            }
             if (k[i].in[1].kind == PG_REF_INT) h_buf = k[i].in[1].index;
+            if (k[i].in[0].kind == PG_REF_INT) broadcast_read.push_back(k[i].in[0].index);       // W: every workgroup reads its own rows while others finish
             held[0] = k[i].out.index;
-            g.dst[0] = 0;
-            g.src0[0] = g.src1[0] = (unsigned char)pgk::kMergeFromMemory;
+            g.dst[np] = 0;
+            g.src0[np] = g.src1[np] = (unsigned char)pgk::kMergeFromMemory;
             written.push_back(k[i].out.index);
-            np = 1;
+            if (k[i].out.index == x_buf) g.rename = x_buf;
+            np++;
             i++;
         }
         while (i < k1 && np < max_phases) {
@@ -344,7 +386,9 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
             const int ob = d.out.index;
             if (std::find(broadcast_read.begin(), broadcast_read.end(), ob) != broadcast_read.end() ||
                 std::find(bc_here.begin(), bc_here.end(), ob) != bc_here.end() || ob == h_buf) ok = false;
+            if (ob == x_buf && ints[ob].numel != n) ok = false;         // would have to rename, and does not rewrite the whole buffer
             if (!ok) break;
+            if (ob == x_buf) g.rename = x_buf;
             // slot for the output: the one that holds the buffer's old contents, else a free one, else
             // the one whose buffer the following kernels need last
             int q_out = -1;
@@ -378,8 +422,31 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, std::vector<MergeGroup
             for (int t = a + 1; t < np; t++)
                 if (k[g.k0 + t].out.index == k[g.k0 + a].out.index) g.store[a] = false;
         }
-        if (head && np == 1) g.head = false;         // no epilogue: the plain GEMV
+        if (head && np == 1) g.head = false;         // no prologue, no epilogue: the plain GEMV
         out.push_back(g);
+    }
+    // every buffer back in its first copy at the end of the segment
+    std::vector<int> odd;
+    for (const auto& g : out)
+        if (g.rename >= 0) {
+            auto it = std::find(odd.begin(), odd.end(), g.rename);
+            if (it == odd.end()) odd.push_back(g.rename); else odd.erase(it);
+        }
+    for (int buf : odd) {
+        int at = -1;
+        for (int gi = 0; gi < (int)out.size(); gi++) if (out[gi].rename == buf) at = gi;
+        MergeGroup rms, rest = out[at];
+        rms.k0 = rest.k0;
+        rms.k1 = rest.k0 + 1;
+        rest.k0++;
+        rest.pro = false;
+        rest.rename = -1;
+        for (int t = 0; t + 1 < MergeGroup::kMax; t++) {
+            rest.src0[t] = rest.src0[t + 1]; rest.src1[t] = rest.src1[t + 1]; rest.dst[t] = rest.dst[t + 1]; rest.store[t] = rest.store[t + 1];
+        }
+        if (rest.k1 - rest.k0 == 1) rest.head = false;
+        out[at] = rest;
+        out.insert(out.begin() + at, rms);
     }
 }
 
@@ -439,7 +506,15 @@ void make_layout(const pg_kernel_desc* k, int nk, const pg_tensor_desc* ext, int
         L.lists.back().ext = v;
     }
     if (eager_only) { L.lists.clear(); L.total = off; return; }
-    for (auto& sg : L.seg) plan_groups(k, sg.k0, sg.k1, sg.groups);
+    L.shadow_off.assign(n_int, kNoShadow);
+    for (auto& sg : L.seg) {
+        plan_groups(k, sg.k0, sg.k1, ints, sg.groups);
+        for (const auto& g : sg.groups)
+            if (g.rename >= 0 && L.shadow_off[g.rename] == kNoShadow) {
+                L.shadow_off[g.rename] = off;
+                off = align_up(off + (size_t)ints[g.rename].numel * elem_bytes(ints[g.rename].dtype));
+            }
+    }
     for (auto& cl : L.lists) {
         build_copy_list(cl, ext, L.ph_off, ws);
         cl.tensors_off = off; off = align_up(off + std::max<size_t>(1, cl.tensors.size()) * sizeof(pgk::CopyTensor));
@@ -504,10 +579,10 @@ pg_status make_records(pg_chain* c) {
             g.launch = pgk::Launch();
             g.launch.block = dim3(256);
             if (g.head) {
-                g.launch.fn = pgk::gemv_epilogue_kernel((int)c->k[g.k0].rows);
+                g.launch.fn = pgk::gemv_epilogue_kernel((int)c->k[g.gemv()].rows, g.pro);
                 g.launch.arg_bytes = sizeof(pgk::GemvEpiArgs);
-                g.launch.grid = c->rec[g.k0].direct.grid;                   // the GEMV's own launch shape: same workgroups, same lanes
-                if (c->rec[g.k0].direct.block.x != 256) return fail(PG_EINVAL, "kernel %d: unexpected GEMV launch shape", g.k0);
+                g.launch.grid = c->rec[g.gemv()].direct.grid;               // the GEMV's own launch shape: same workgroups, same lanes
+                if (c->rec[g.gemv()].direct.block.x != 256) return fail(PG_EINVAL, "kernel %d: unexpected GEMV launch shape", g.gemv());
             } else {
                 g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype);
                 g.launch.arg_bytes = sizeof(pgk::MergedArgs);
@@ -732,26 +807,54 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
     if (kind == kGraphTableMemcpyNode)   // the graph's first node copies the pointers from its instance's pinned staging
         le = hipMemcpyAsync(c->ws + c->table_off, c->alt[0].host[inst], c->ext.size() * 8, hipMemcpyHostToDevice, s);
     auto block_of = [&](KernelRec& r) -> ArgBlock& { return kind == kGraphCopy ? r.a_copy : kind == kGraphHostTable ? r.a_host[inst] : r.a_ind; };
+    // Which copy of each internal buffer is current (see plan_groups: runs that rename).  Every kernel of
+    // the segment gets its internal operands in the current copy; all are back in the first at the end.
+    std::vector<char> second(c->ints.size(), 0);
+    auto in_copy = [&](int buf, bool use_second) -> char* { return c->ws + (use_second ? c->shadow_off[buf] : c->int_off[buf]); };
+    auto versioned = [&](int ki, const MergeGroup* grp) -> ArgBlock {     // kernel ki's argument block for this graph
+        KernelRec& r = c->rec[ki];
+        const pg_kernel_desc& d = c->k[ki];
+        ArgBlock a = block_of(r);
+        for (int j = 0; j < r.n_in; j++)
+            if (d.in[j].kind == PG_REF_INT && second[d.in[j].index]) a.ptr[1 + j] = in_copy(d.in[j].index, true);
+        const bool renamed = grp && grp->rename == d.out.index && ki >= grp->gemv();
+        if (second[d.out.index] != renamed) a.ptr[0] = in_copy(d.out.index, true);
+        return a;
+    };
     for (auto& grp : sg.groups) {
         if (le != hipSuccess) break;
         if (!c->merge || grp.k1 - grp.k0 < 2) {
             for (int i = grp.k0; i < grp.k1 && le == hipSuccess; i++) {
                 KernelRec& r = c->rec[i];
-                le = launch(kind == kGraphCopy ? r.direct : r.indirect, &block_of(r), s);
+                ArgBlock a = versioned(i, nullptr);
+                le = launch(kind == kGraphCopy ? r.direct : r.indirect, &a, s);
             }
             continue;
         }
         if (grp.head) {
-            // the GEMV's dispatch with the following elementwise kernels as its epilogue
+            // the GEMV's dispatch with the following elementwise kernels as its epilogue (and the RMSNorm before it as its prologue)
             pgk::GemvEpiArgs e;
             memset(&e, 0, sizeof e);
-            KernelRec& hr = c->rec[grp.k0];
-            e.g = block_of(hr).gemv;
-            e.head = (kind == kGraphCopy ? 0u : (unsigned)hr.ind_mask) | ((unsigned)grp.dst[0] << 8) | (grp.store[0] ? 1u << 16 : 0u);
-            for (int i = grp.k0 + 1; i < grp.k1; i++, e.n_epi++) {
+            const int hk = grp.gemv();
+            KernelRec& hr = c->rec[hk];
+            const ArgBlock ha = versioned(hk, &grp);
+            e.g = ha.gemv;
+            e.head = (kind == kGraphCopy ? 0u : (unsigned)hr.ind_mask) | ((unsigned)grp.dst[hk - grp.k0] << 8) |
+                     (grp.store[hk - grp.k0] ? pgk::kEpiHeadStore : 0u);
+            if (grp.pro) {
+                KernelRec& pr = c->rec[grp.k0];
+                const ArgBlock pa = versioned(grp.k0, &grp);
+                e.x = pa.ptr[1];
+                e.gain = pa.ptr[2];
+                e.eps = c->k[grp.k0].eps;
+                e.head |= pgk::kEpiPrologue | pgk::kEpiStoreH;
+                if (kind != kGraphCopy) e.head |= ((pr.ind_mask & 1) ? pgk::kEpiXSlot : 0u) | ((pr.ind_mask & 2) ? pgk::kEpiGainSlot : 0u);
+                // e.g.h is the RMSNorm's output in its current copy: where workgroup 0 stores the normalised rows
+            }
+            for (int i = hk + 1; i < grp.k1; i++, e.n_epi++) {
                 KernelRec& r = c->rec[i];
                 const pg_kernel_desc& d = c->k[i];
-                const ArgBlock& a = block_of(r);
+                const ArgBlock a = versioned(i, &grp);
                 const int t = i - grp.k0;
                 pgk::MergePhase& ph = e.ph[e.n_epi];
                 ph.out = const_cast<void*>(a.ptr[0]);
@@ -763,6 +866,7 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
             }
             for (int q = e.n_epi; q < pgk::kEpiMaxPhases; q++) e.ph[q].meta = (unsigned)PG_GELU;   // operands "from slot 0": fetches nothing, never played
             le = launch(grp.launch, &e, s);
+            if (grp.rename >= 0) second[grp.rename] ^= 1;
             continue;
         }
         // one dispatch for the run: the kernels' own operands, in order, in one argument struct
@@ -772,7 +876,7 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
         for (int i = grp.k0; i < grp.k1; i++, m.n_phase++) {
             KernelRec& r = c->rec[i];
             const pg_kernel_desc& d = c->k[i];
-            const ArgBlock& a = block_of(r);
+            const ArgBlock a = versioned(i, nullptr);
             pgk::MergePhase& ph = m.ph[m.n_phase];
             ph.out = const_cast<void*>(a.ptr[0]);
             ph.in0 = a.ptr[1];
@@ -785,6 +889,8 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
         for (int q = m.n_phase; q < pgk::kMergeMaxPhases; q++) m.ph[q].meta = (unsigned)PG_GELU;   // operands "from slot 0": fetches nothing, never played
         le = launch(grp.launch, &m, s);
     }
+    for (char v : second)
+        if (v && le == hipSuccess) le = hipErrorAssert;     // plan_groups pairs the renames up; never reached
     hipGraph_t g = nullptr;
     hipError_t ee = hipStreamEndCapture(s, &g);   // always end the capture, even after a failed launch
     if (le != hipSuccess) { if (g) (void)hipGraphDestroy(g); g_hip_err = (int)le; return fail(PG_EHIP, "kernel launch during capture failed: %s", hipGetErrorString(le)); }
@@ -914,6 +1020,7 @@ pg_status build_chain(const pg_kernel_desc* kernels, int32_t nk, const pg_tensor
     }
     c->ph_off = std::move(L.ph_off);
     c->int_off = std::move(L.int_off);
+    c->shadow_off = std::move(L.shadow_off);
     c->table_off = L.table_off;
     c->copy_lists = std::move(L.lists);
     c->seg = std::move(L.seg);

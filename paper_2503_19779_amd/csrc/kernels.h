@@ -109,10 +109,25 @@ struct MergedArgs {
 // another's results, so nothing has to be waited for.
 constexpr int kEpiMaxPhases = 3;
 constexpr unsigned kEpiStore = 1u << 8;   // MergePhase::ind: this kernel's output is stored (no later kernel of the run overwrites it)
+// And the RMSNorm in front of the GEMV can ride along as a prologue: every workgroup of the GEMV needs the
+// whole normalised vector anyway, so each one normalises the rows itself (the stand-alone kernel's
+// arithmetic, lane t holding vector t of a row -- exactly where the GEMV wants h in LDS) while its
+// weights are on their way, and workgroup 0 stores the result where the RMSNorm kernel would have.
+// A kernel of the epilogue may update the normalised stream in place (the residual add does); the
+// runtime then lets it write a shadow copy of that buffer instead, so that no workgroup can read an
+// element another one has already replaced (chain.hip: versions).
+constexpr unsigned kEpiHeadStore = 1u << 16;    // GemvEpiArgs::head: store the GEMV's result
+constexpr unsigned kEpiPrologue = 1u << 17;     // h is not loaded but computed: RMSNorm of x with gain and eps
+constexpr unsigned kEpiXSlot = 1u << 18, kEpiGainSlot = 1u << 19;   // x / gain are pointer-table slots
+constexpr unsigned kEpiStoreH = 1u << 20;       // workgroup 0 stores the normalised rows to g.h
 struct GemvEpiArgs {
-    GemvArgs g;
-    unsigned head;          // bit 0 / 1: W / h are pointer-table slots; bits 8-15: slot that keeps the GEMV's result; bit 16: store it
+    GemvArgs g;             // with a prologue g.h is where the normalised rows are stored, not read
+    unsigned head;          // bit 0 / 1: W / h are pointer-table slots; bits 8-15: slot that keeps the GEMV's result; bits 16-20 above
     int n_epi;
+    const void* x;          // prologue: [rows, cols] to normalise
+    const void* gain;       // prologue: [cols]
+    float eps;
+    int reserved;
     MergePhase ph[kEpiMaxPhases];   // m: period of in1 (rows * n = element for element)
 };
 
@@ -143,6 +158,6 @@ bool merge_candidate(int op, int dtype, const Shape& shape, bool whole_vectors, 
 const void* merged_kernel(int dtype);
 // Is this the GEMV shape k_gemv_shared<bf16, ., 2, rows> serves (the one the epilogue form exists for)?
 bool merge_head(int op, int dtype, const Shape& shape, long long* n_out);
-const void* gemv_epilogue_kernel(int rows_of_h);
+const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue);
 
 }  // namespace pgk

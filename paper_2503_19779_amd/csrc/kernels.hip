@@ -245,6 +245,12 @@ __device__ __forceinline__ float wave_sum(float v) {
     return ((r0 + r1) + r2) + r3;
 }
 
+// Workgroup barrier for an exchange through LDS only: waits for this wave's LDS operations, not for its
+// outstanding global stores (which __syncthreads would, at about a microsecond apiece).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // ---- elementwise ----------------------------------------------------------------------------
 // GELU(a) = a * Phi(a) with Phi(a) = erfc(-a / sqrt 2) / 2 (keeps relative accuracy in the left
 // tail).  For fp32 tensors it is evaluated in fp64 and rounded once, so that the result is the
@@ -594,17 +600,24 @@ static_assert(kBlock == 64 * kGemvChunk, "one vector of h per lane of the workgr
 // in every lane.
 // GLOBAL: W and h reached the kernel as generic pointers (through a run-time choice); fetch them with loads
 // that say "global memory" outright.
-template <typename T, int R, int RB, bool AL, bool GLOBAL, class Hook>
+// PRO: h is not loaded but computed here -- `h` points at the rows x to normalise, `gain` and `eps` are
+// RMSNorm's; the arithmetic is rms_body's for a row of one vector per lane (fused multiply-add sum of
+// squares in element order, wave_sum, the four wave sums added in a fixed order through LDS,
+// 1 / sqrt(mean + eps), (x * scale) * gain, one rounding), and lane t's vector of the result goes where
+// lane t's vector of h would have gone.  hstore != nullptr: this workgroup also stores the rows there.
+template <typename T, int R, int RB, bool AL, bool GLOBAL, bool PRO, class Hook>
 __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */,
-                                                 Hook after_issue, float (*sums)[RB]) {
+                                                 Hook after_issue, float (*sums)[RB],
+                                                 const T* gain = nullptr, float eps = 0.f, T* hstore = nullptr, float* part = nullptr) {
     constexpr int NV = Vec<T, 16>::NV;
     constexpr int kCols = 64 * kGemvChunk * NV;
-    unsigned hv[RB][4], ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4];
+    unsigned hv[RB][4], ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4], wg[4];
 #pragma unroll
     for (int rr = 0; rr < RB; rr++) {
         if constexpr (GLOBAL) load_vec_global<T, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
         else load_vec<T, 16, AL, false>(h + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
     }
+    if constexpr (PRO) load_vec_global<T, AL, false>(gain + (size_t)tid * NV, wg);
     __builtin_amdgcn_sched_barrier(0);   // h first: loads come back in the order they were issued
 #pragma unroll
     for (int r = 0; r < R; r++) {
@@ -617,6 +630,27 @@ __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, 
     }
     __builtin_amdgcn_sched_barrier(0);
     after_issue();
+    if constexpr (PRO) {
+        float fg[NV];
+        Vec<T, 16>::unpack(wg, fg);
+#pragma unroll
+        for (int rr = 0; rr < RB; rr++) {
+            float fx[NV], fo[NV];
+            Vec<T, 16>::unpack(hv[rr], fx);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fx[e], fx[e], acc);
+            acc = wave_sum(acc);
+            if ((tid & 63) == 0) part[tid >> 6] = acc;
+            lds_barrier();
+            const float total = ((part[0] + part[1]) + part[2]) + part[3];
+            lds_barrier();                                         // `part` is free for the next row
+            const float scale = 1.0f / sqrtf(total / (float)kCols + eps);
+#pragma unroll
+            for (int e = 0; e < NV; e++) fo[e] = (fx[e] * scale) * fg[e];
+            Vec<T, 16>::pack(fo, hv[rr]);
+        }
+    }
 #pragma unroll
     for (int rr = 0; rr < RB; rr++) {
         v4u t;
@@ -624,6 +658,11 @@ __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, 
         hs[rr * kBlock + tid] = t;
     }
     __syncthreads();      // every wave of the workgroup gets here: none leaves early
+    if constexpr (PRO) {  // after the barrier, which would otherwise wait for these stores
+        if (hstore)
+#pragma unroll
+            for (int rr = 0; rr < RB; rr++) store_vec_global(hstore + (size_t)rr * kCols + (size_t)tid * NV, hv[rr]);
+    }
 #pragma unroll
     for (int rr = 0; rr < RB; rr++)
 #pragma unroll
@@ -649,7 +688,7 @@ __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, 
 template <typename T, int R, int RB, bool AL>
 __device__ __forceinline__ void gemv_body_shared(const T* W, const T* h, T* y, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */) {
     float sums[R][RB];
-    gemv_sums_shared<T, R, RB, AL, false>(W, h, n, j0, lane, tid, hs, [] {}, sums);
+    gemv_sums_shared<T, R, RB, AL, false, false>(W, h, n, j0, lane, tid, hs, [] {}, sums);
 #pragma unroll
     for (int rr = 0; rr < RB; rr++)
 #pragma unroll
@@ -1053,12 +1092,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
 // over the kernels that picks its operands out of the fetched vectors and the register slots with
 // conditional moves.  Code size counts: the kernel runs once per dispatch on a CU whose instruction
 // cache has most likely never seen it, so every 64 bytes on the executed path are a fetch from memory.
-//
-// Workgroup barrier for an exchange through LDS only: waits for this wave's LDS operations, not for its
-// outstanding global stores (which __syncthreads would, at about a microsecond apiece).
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 template <typename T, bool AL>
 __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const* in0, const T* const* in1, float* part) {
@@ -1214,7 +1247,7 @@ __global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
 
 // GEMV with an elementwise epilogue: k_gemv_shared's body, then lane e of each wave plays output e through
 // the kernels that follow (see kernels.h).  bf16 only.
-template <int RB>
+template <int RB, bool PRO>
 __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
     constexpr int P = kEpiMaxPhases;
     // The GEMV's own arguments first, in one batch of scalar loads (see args_up_front): nothing else stands
@@ -1229,9 +1262,13 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
     bf16_t* outs[P];
     unsigned ms[P], metas[P], inds[P];
     const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, head & 1));
-    const bf16_t* h = static_cast<const bf16_t*>(resolve_rt(p.g.h, head & 2));
+    // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where workgroup 0 stores it
+    const bf16_t* h = static_cast<const bf16_t*>(PRO ? resolve_rt(p.x, head & kEpiXSlot) : resolve_rt(p.g.h, head & 2));
+    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(resolve_rt(p.gain, head & kEpiGainSlot)) : nullptr;
+    bf16_t* hstore = (PRO && (head & kEpiStoreH) && blockIdx.x == 0) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
     bf16_t* y = static_cast<bf16_t*>(p.g.out);
     __shared__ v4u hs[RB * kBlock];
+    __shared__ float part[kBlock / 64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = p.g.n;
     const int j0 = (blockIdx.x * (kBlock / 64) + (tid >> 6)) * 2;
@@ -1267,8 +1304,10 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
         }
     };
     float sums[2][RB];
-    if (aligned_to(W, 16) && aligned_to(h, 16)) gemv_sums_shared<bf16_t, 2, RB, true, true>(W, h, n, j0, lane, tid, hs, fetch, sums);
-    else gemv_sums_shared<bf16_t, 2, RB, false, true>(W, h, n, j0, lane, tid, hs, fetch, sums);
+    if (aligned_to(W, 16) && aligned_to(h, 16) && (!PRO || aligned_to(gain, 16)))
+        gemv_sums_shared<bf16_t, 2, RB, true, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, p.eps, hstore, part);
+    else
+        gemv_sums_shared<bf16_t, 2, RB, false, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, p.eps, hstore, part);
     float v = sums[0][0];
 #pragma unroll
     for (int rr = 0; rr < RB; rr++)
@@ -1276,7 +1315,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
         for (int r = 0; r < 2; r++)
             if (lane == rr * 2 + r) v = sums[r][rr];
     unsigned bits = f32_to_bf16(v);
-    if (mine && (head & (1u << 16))) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx) = (unsigned short)bits;
+    if (mine && (head & kEpiHeadStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx) = (unsigned short)bits;
     float slot[kMergeSlots];
 #pragma unroll
     for (int q = 0; q < kMergeSlots; q++) slot[q] = 0.f;
@@ -1655,12 +1694,16 @@ bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
     return true;
 }
 
-const void* gemv_epilogue_kernel(int rows_of_h) {
-    switch (rows_of_h) {
-    case 1: return reinterpret_cast<const void*>(&k_gemv_epilogue<1>);
-    case 2: return reinterpret_cast<const void*>(&k_gemv_epilogue<2>);
-    case 3: return reinterpret_cast<const void*>(&k_gemv_epilogue<3>);
-    case 4: return reinterpret_cast<const void*>(&k_gemv_epilogue<4>);
+const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue) {
+    switch (rows_of_h * 2 + (with_prologue ? 1 : 0)) {
+    case 2: return reinterpret_cast<const void*>(&k_gemv_epilogue<1, false>);
+    case 3: return reinterpret_cast<const void*>(&k_gemv_epilogue<1, true>);
+    case 4: return reinterpret_cast<const void*>(&k_gemv_epilogue<2, false>);
+    case 5: return reinterpret_cast<const void*>(&k_gemv_epilogue<2, true>);
+    case 6: return reinterpret_cast<const void*>(&k_gemv_epilogue<3, false>);
+    case 7: return reinterpret_cast<const void*>(&k_gemv_epilogue<3, true>);
+    case 8: return reinterpret_cast<const void*>(&k_gemv_epilogue<4, false>);
+    case 9: return reinterpret_cast<const void*>(&k_gemv_epilogue<4, true>);
     default: return nullptr;
     }
 }

@@ -3,6 +3,8 @@ handed on in registers) leaves the same bits behind as eager launches and as the
 per kernel -- at every batch size that merges, with external and broadcast operands inside a run, with
 more live buffers than register slots, and on chains where a run must be cut because a kernel re-reads
 a buffer in another pattern than element for element."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -29,8 +31,10 @@ def test_merged_graphs_equal_eager_and_unmerged_graphs(batch):
     spec = decode_chain(batch=batch, layers=3, blocks_per_layer=4, hidden=2048, n_ext=6)
     h = Harness(spec, capture=False)
     merged, unmerged = h.chain.graph_dispatches()
-    # per sub-block the RMSNorm and one dispatch for the GEMV with GELU, add (and input add) as its epilogue
-    assert unmerged == len(spec.kernels) and merged == 2 * 12, (merged, unmerged)
+    # per sub-block one dispatch: the GEMV with the RMSNorm as its prologue and GELU, add (and input add) as its
+    # epilogue.  Sub-blocks 1..11 overwrite the stream they normalise and write its other copy; eleven is odd,
+    # so the last of them is split into RMSNorm + GEMV dispatch and leaves the stream in its first copy.
+    assert unmerged == len(spec.kernels) and merged == 12 + 1, (merged, unmerged)
     h.chain.capture(h.stream)
     x_np, x_dev = h.inputs(0)
     want = h.oracle(x_np)[0]
@@ -46,6 +50,98 @@ def test_merged_graphs_equal_eager_and_unmerged_graphs(batch):
     h.chain.capture(h.stream)
     off = _all_modes(h, x_dev)
     assert same_bits(off["copy"][0], ref) and same_bits(off["indirect"][0], ref)
+    h.close()
+
+
+@pytest.mark.parametrize("batch,cuts", [(1, (5,)), (2, (4, 9)), (4, (1, 2, 3))])
+def test_prologue_runs_leave_every_segment_in_the_first_copy(batch, cuts):
+    """The decode chain cut into segments after the given sub-blocks: a segment with an odd number of
+    renaming runs splits its last one, so that any mixture of modes per segment (eager reads and writes the
+    first copy only) sees the stream where it expects it; the step-by-step check pins every kernel."""
+    spec = decode_chain(batch=batch, layers=2, blocks_per_layer=5, hidden=2048, n_ext=4)
+    ks, seg, sub = [], 0, -1
+    for k in spec.kernels:
+        if k.op == "rmsnorm":
+            sub += 1
+            if sub in cuts:
+                seg += 1
+        ks.append(dataclasses.replace(k, segment=seg))
+    spec = ChainSpec(spec.name + "_cut", ks, spec.ext, spec.ints, spec.weights, spec.outputs, spec.seed, meta=dict(spec.meta))
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
+    assert merged < 2 * 10
+    h.chain.capture(h.stream)
+    n_seg = len(cuts) + 1
+    for t in range(4):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        assert same_bits(outs["eager"][0], outs["copy"][0]) and same_bits(outs["eager"][0], outs["indirect"][0]), t
+        for pattern in range(3 ** n_seg if n_seg <= 3 else 0, 0, -7):      # a spread of per-segment mode mixtures
+            modes = [(pattern // 3 ** i) % 3 for i in range(n_seg)]
+            modes[0] = modes[0] or 1
+            # a segment without external operands has no indirect mode
+            modes = [m if (m != 2 or _seg_has_ext(spec, i)) else 1 for i, m in enumerate(modes)]
+            h.scrub()
+            assert same_bits(h.run("selected", x_dev, modes)[0], outs["eager"][0]), (t, modes)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
+    h.close()
+
+
+def _seg_has_ext(spec, seg):
+    return any(r.kind == EXT for k in spec.kernels if k.segment == seg for r in k.ins)
+
+
+@pytest.mark.parametrize("rows", [1, 3])
+def test_prologue_hazards(rows):
+    """RMSNorm -> GEMV pairs whose neighbours make the prologue form harder: (a) the GEMV itself overwrites
+    the normalised stream; (b) the stream's buffer is larger than what the run rewrites (no renaming: the run
+    must not take the prologue form and overwrite x, or else keep the rest of the buffer visible); (c) a
+    kernel of the epilogue reads the normalised rows back (stored by one workgroup only: must be cut);
+    (d) the gain comes from an internal buffer; (e) x and the gain are external."""
+    H = 2048
+    N = rows * H
+    X, T1, T2, BIG, G = 0, 1, 2, 3, 4
+    ks = [KernelSpec("add", "bf16", X, (Ref(EXT, 0), Ref(EXT, 0)), N, m=N),                                   # x = 2 e0
+          KernelSpec("add", "bf16", BIG, (Ref(EXT, 2), Ref(EXT, 2)), 2 * N, m=2 * N),                         # big = 2 e2   (2N elements)
+          KernelSpec("mul", "bf16", G, (Ref(WEIGHT, 1), Ref(WEIGHT, 1)), H, m=H),                             # g = w1^2
+          # (e) external x and gain, epilogue writes x's internal namesake
+          KernelSpec("rmsnorm", "bf16", T1, (Ref(EXT, 0), Ref(EXT, 1)), H, rows=rows, cols=H, eps=1e-6),
+          KernelSpec("gemv", "bf16", T2, (Ref(WEIGHT, 0), Ref(INT, T1)), H, rows=rows, cols=H),
+          KernelSpec("add", "bf16", X, (Ref(INT, X), Ref(INT, T2)), N, m=N),
+          # (a) the GEMV writes x
+          KernelSpec("rmsnorm", "bf16", T1, (Ref(INT, X), Ref(WEIGHT, 1)), H, rows=rows, cols=H, eps=1e-6),
+          KernelSpec("gemv", "bf16", X, (Ref(WEIGHT, 0), Ref(INT, T1)), H, rows=rows, cols=H),
+          KernelSpec("gelu", "bf16", X, (Ref(INT, X),), N),
+          # (d) gain from an internal buffer, (c) the epilogue's second kernel reads T1 back
+          KernelSpec("rmsnorm", "bf16", T1, (Ref(INT, X), Ref(INT, G)), H, rows=rows, cols=H, eps=1e-6),
+          KernelSpec("gemv", "bf16", T2, (Ref(WEIGHT, 0), Ref(INT, T1)), H, rows=rows, cols=H),
+          KernelSpec("add", "bf16", X, (Ref(INT, X), Ref(INT, T2)), N, m=N),
+          KernelSpec("add", "bf16", T2, (Ref(INT, T2), Ref(INT, T1)), N, m=N),
+          # (b) normalise the head of the big buffer, then overwrite that head
+          KernelSpec("rmsnorm", "bf16", T1, (Ref(INT, BIG), Ref(WEIGHT, 1)), H, rows=rows, cols=H, eps=1e-6),
+          KernelSpec("gemv", "bf16", T2, (Ref(WEIGHT, 0), Ref(INT, T1)), H, rows=rows, cols=H),
+          KernelSpec("add", "bf16", BIG, (Ref(INT, BIG), Ref(INT, T2)), N, m=N),
+          KernelSpec("add", "bf16", BIG, (Ref(INT, BIG), Ref(EXT, 2)), 2 * N, m=2 * N),                       # reads the tail the run left alone
+          ]
+    spec = ChainSpec(f"prologue_hazards_{rows}", ks,
+                     [TensorSpec("bf16", N), TensorSpec("bf16", H, ("normal", 1.0, 0.1)), TensorSpec("bf16", 2 * N)],
+                     [TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", 2 * N), TensorSpec("bf16", H)],
+                     [TensorSpec("bf16", H * H, ("normal", 0.0, 0.02)), TensorSpec("bf16", H, ("normal", 1.0, 0.1))],
+                     [X, T1, T2, BIG], 6010)
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
+    assert merged < unmerged
+    h.chain.capture(h.stream)
+    for t in range(3):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        for o in range(len(spec.outputs)):
+            assert same_bits(outs["eager"][o], outs["copy"][o]) and same_bits(outs["eager"][o], outs["indirect"][o]), (t, o)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
     h.close()
 
 
