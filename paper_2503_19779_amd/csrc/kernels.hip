@@ -19,6 +19,8 @@
 // written.
 #include "kernels.h"
 
+#include <cstddef>
+
 namespace pgk {
 namespace {
 
@@ -145,6 +147,13 @@ template <typename T>
 __device__ __forceinline__ unsigned load_raw_global(const T* p) {
     if constexpr (sizeof(T) == 4) return *(const unsigned PG_GLOBAL*)(uintptr_t)p;
     else return *(const unsigned short PG_GLOBAL*)(uintptr_t)p;
+}
+// Element i of a tensor whose address is the same in every lane: the address stays in scalar registers and
+// the load takes the lane's offset beside it, with no vector arithmetic on 64-bit addresses.
+template <typename T>
+__device__ __forceinline__ unsigned load_raw_global_at(const T* base, unsigned i) {
+    if constexpr (sizeof(T) == 4) return ((const unsigned PG_GLOBAL*)(uintptr_t)base)[i];
+    else return ((const unsigned short PG_GLOBAL*)(uintptr_t)base)[i];
 }
 __device__ __forceinline__ void store_vec_global(void* p, const unsigned* w) {
     v4u t;
@@ -340,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void k_elementwise(EwArgs p) {
     const IdxT n = (IdxT)p.n, m = (IdxT)p.m;
     const bool b_vec = kBinary && (m % NV) == 0;      // then a vector of b never wraps around the period
     const bool al = aligned_to(a, VB) && (!b_vec || aligned_to(b, VB));
-    if (al) ew_body<T, OP, VB, U, IdxT, true>(a, b, o, n, m, b_vec, blockIdx.x);
+    if (__builtin_expect(al, 1)) ew_body<T, OP, VB, U, IdxT, true>(a, b, o, n, m, b_vec, blockIdx.x);
     else ew_body<T, OP, VB, U, IdxT, false>(a, b, o, n, m, b_vec, blockIdx.x);
 }
 
@@ -493,7 +502,7 @@ __device__ __forceinline__ void rms_row(const T* x0, const T* g, T* o0, int cols
     // rows of an aligned buffer stay aligned when cols is a multiple of the vector; else check this row
     const bool al = aligned_to(x, 16) && aligned_to(g, 16);
     const bool al_o = aligned_to(o, 16);
-    if (al) rms_body<T, VPT, RAGGED, true>(x, g, o, cols, eps, al_o, part);
+    if (__builtin_expect(al, 1)) rms_body<T, VPT, RAGGED, true>(x, g, o, cols, eps, al_o, part);
     else rms_body<T, VPT, RAGGED, false>(x, g, o, cols, eps, al_o, part);
 }
 
@@ -583,7 +592,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
     if (j0 >= p.n) return;   // whole wave leaves together
     // row starts of W stay aligned only if cols is a multiple of the vector
     const bool al = RS != 2 && aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemv_body<T, R, RS, true>(W, h, y, p.n, p.cols, j0, lane);
+    if (__builtin_expect(al, 1)) gemv_body<T, R, RS, true>(W, h, y, p.n, p.cols, j0, lane);
     else gemv_body<T, R, RS, false>(W, h, y, p.n, p.cols, j0, lane);
 }
 
@@ -596,8 +605,10 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs p) {
 // gemvb_body: the results are bit-identical.
 static_assert(kBlock == 64 * kGemvChunk, "one vector of h per lane of the workgroup");
 // `after_issue()` runs once every weight load of the wave has been asked for (the epilogue form of the
-// kernel fetches its own operands there); sums[r][rr] receives the finished dot products, the same bits
-// in every lane.
+// kernel fetches its own operands there: every instruction in front of the weight loads delays the whole
+// kernel -- asking for the epilogue's operands first, so that they would be back before the weights,
+// measured 0.17 us slower per launch); sums[r][rr] receives the finished dot products, the same bits in
+// every lane.
 // GLOBAL: W and h reached the kernel as generic pointers (through a run-time choice); fetch them with loads
 // that say "global memory" outright.
 // PRO: h is not loaded but computed here -- `h` points at the rows x to normalise, `gain` and `eps` are
@@ -605,10 +616,11 @@ static_assert(kBlock == 64 * kGemvChunk, "one vector of h per lane of the workgr
 // squares in element order, wave_sum, the four wave sums added in a fixed order through LDS,
 // 1 / sqrt(mean + eps), (x * scale) * gain, one rounding), and lane t's vector of the result goes where
 // lane t's vector of h would have gone.  hstore != nullptr: this workgroup also stores the rows there.
+// (eps by reference: the epilogue kernel reads it from its arguments inside the hook.)
 template <typename T, int R, int RB, bool AL, bool GLOBAL, bool PRO, class Hook>
 __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, int j0, int lane, int tid, v4u* hs /* [RB][kBlock] */,
                                                  Hook after_issue, float (*sums)[RB],
-                                                 const T* gain = nullptr, float eps = 0.f, T* hstore = nullptr, float* part = nullptr) {
+                                                 const T* gain = nullptr, const float& eps = 0.f, T* hstore = nullptr, float* part = nullptr) {
     constexpr int NV = Vec<T, 16>::NV;
     constexpr int kCols = 64 * kGemvChunk * NV;
     unsigned hv[RB][4], ww[R][kGemvChunk][4], wh[RB][kGemvChunk][4], wg[4];
@@ -641,10 +653,10 @@ __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, 
 #pragma unroll
             for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fx[e], fx[e], acc);
             acc = wave_sum(acc);
-            if ((tid & 63) == 0) part[tid >> 6] = acc;
+            float* prow = part + rr * (kBlock / 64);               // a row of partial sums per row of x: one barrier each
+            if ((tid & 63) == 0) prow[tid >> 6] = acc;
             lds_barrier();
-            const float total = ((part[0] + part[1]) + part[2]) + part[3];
-            lds_barrier();                                         // `part` is free for the next row
+            const float total = ((prow[0] + prow[1]) + prow[2]) + prow[3];
             const float scale = 1.0f / sqrtf(total / (float)kCols + eps);
 #pragma unroll
             for (int e = 0; e < NV; e++) fo[e] = (fx[e] * scale) * fg[e];
@@ -707,7 +719,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv_shared(GemvArgs p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int j0 = (blockIdx.x * (kBlock / 64) + (tid >> 6)) * R;
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemv_body_shared<T, R, RB, true>(W, h, y, p.n, j0, lane, tid, hs);
+    if (__builtin_expect(al, 1)) gemv_body_shared<T, R, RB, true>(W, h, y, p.n, j0, lane, tid, hs);
     else gemv_body_shared<T, R, RB, false>(W, h, y, p.n, j0, lane, tid, hs);
 }
 
@@ -777,7 +789,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv_batched(GemvArgs p) {
     const int j0 = (blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * R;
     if (j0 >= p.n) return;
     const bool al = RS != 2 && aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemvb_body<T, R, RB, RS, true>(W, h, y, p.rows, p.n, p.cols, j0, lane);
+    if (__builtin_expect(al, 1)) gemvb_body<T, R, RB, RS, true>(W, h, y, p.rows, p.n, p.cols, j0, lane);
     else gemvb_body<T, R, RB, RS, false>(W, h, y, p.rows, p.n, p.cols, j0, lane);
 }
 
@@ -992,7 +1004,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16_narrow(GemvArgs p)
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemm_mfma_narrow_body<FULL, true, NRH>(W, h, y, p.rows, p.n, p.cols, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<FULL, true, NRH>(W, h, y, p.rows, p.n, p.cols, stage, red);
     else gemm_mfma_narrow_body<FULL, false, NRH>(W, h, y, p.rows, p.n, p.cols, stage, red);
 }
 
@@ -1064,7 +1076,7 @@ __global__ __launch_bounds__(kBlock, 1) void k_gemm_mfma_bf16_wide(GemvArgs p) {
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[2 * 4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);
-    if (al) gemm_mfma_wide_body<true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
     else gemm_mfma_wide_body<false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
@@ -1076,7 +1088,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);   // rows keep the alignment: cols is a multiple of 8
-    if (al) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
     else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
@@ -1241,7 +1253,7 @@ __global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
             al = al && aligned_to(in1[i], 16);
         }
     }
-    if (al) merged_body<T, true>(p, in0, in1, part);
+    if (__builtin_expect(al, 1)) merged_body<T, true>(p, in0, in1, part);
     else merged_body<T, false>(p, in0, in1, part);
 }
 
@@ -1253,61 +1265,133 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
     // The GEMV's own arguments first, in one batch of scalar loads (see args_up_front): nothing else stands
     // between the start of the kernel and the weight loads.  The epilogue's table is read once those are on
     // their way (`fetch`), and kept in scalar registers from then on.
-    args_up_front(p.g);
+    // The first 64 bytes of the arguments hold everything that is needed before the weight loads can go out,
+    // and only those are waited for here, in one batch of scalar loads (see args_up_front; the start of the
+    // argument buffer arrives in under 0.1 us, the lines behind it take 0.3 us more).  The epilogue's table
+    // and eps are read once the weights are on their way (`fetch`).
+    static_assert(offsetof(GemvEpiArgs, gain) + sizeof(void*) == 64, "what the kernel needs first sits in the first 64 bytes");
+    const void* Wa = p.g.W;
+    const void* ha = p.g.h;
+    bf16_t* y = static_cast<bf16_t*>(p.g.out);
+    int n = p.g.n;
     unsigned head = p.head;
-    asm volatile("" : "+s"(head));
-    int n_epi = 0;
+    int n_epi = p.n_epi;
+    const void* xa = p.x;
+    const void* ga = p.gain;
+    asm volatile("" : "+s"(Wa), "+s"(ha), "+s"(y), "+s"(n), "+s"(head), "+s"(n_epi), "+s"(xa), "+s"(ga));
     const void* a0[P];
     const void* a1[P];
     bf16_t* outs[P];
     unsigned ms[P], metas[P], inds[P];
-    const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, head & 1));
+    float eps = 0.f;
+    static_assert(P == 3, "the argument batch in fetch names every phase");
+    const void PG_CONSTANT* const ka = (const void PG_CONSTANT*)__builtin_amdgcn_kernarg_segment_ptr();   // a readable address for a load whose result is not used
+    using SlotPtr = const void* const PG_CONSTANT*;
+    auto slot_addr = [&](const void* q, bool is_slot) -> SlotPtr { return is_slot ? (SlotPtr)(uintptr_t)q : (SlotPtr)ka; };
     // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where workgroup 0 stores it
-    const bf16_t* h = static_cast<const bf16_t*>(PRO ? resolve_rt(p.x, head & kEpiXSlot) : resolve_rt(p.g.h, head & 2));
-    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(resolve_rt(p.gain, head & kEpiGainSlot)) : nullptr;
-    bf16_t* hstore = (PRO && (head & kEpiStoreH) && blockIdx.x == 0) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
-    bf16_t* y = static_cast<bf16_t*>(p.g.out);
+    if (head & (1u | (PRO ? kEpiXSlot | kEpiGainSlot : 2u))) {      // some operand is a pointer-table slot: all in one batch, without branches
+        const bool sw = head & 1u, sh = head & (PRO ? kEpiXSlot : 2u), sg = PRO && (head & kEpiGainSlot);
+        SlotPtr aw = slot_addr(Wa, sw), ah = slot_addr(PRO ? xa : ha, sh), ag = slot_addr(ga, sg);
+        const void* tw = *aw;
+        const void* th = *ah;
+        const void* tg = PRO ? *ag : nullptr;
+        asm volatile("" : "+s"(tw), "+s"(th), "+s"(tg));
+        if (sw) Wa = tw;
+        if (sh) { if (PRO) xa = th; else ha = th; }
+        if (sg) ga = tg;
+    }
+    const bf16_t* W = static_cast<const bf16_t*>(Wa);
+    const bf16_t* h = static_cast<const bf16_t*>(PRO ? xa : ha);
+    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(ga) : nullptr;
+    bf16_t* hstore = (PRO && (head & kEpiStoreH) && blockIdx.x == 0) ? static_cast<bf16_t*>(const_cast<void*>(ha)) : nullptr;
     __shared__ v4u hs[RB * kBlock];
-    __shared__ float part[kBlock / 64];
+    __shared__ float part[RB * (kBlock / 64)];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int n = p.g.n;
     const int j0 = (blockIdx.x * (kBlock / 64) + (tid >> 6)) * 2;
-    const bool mine = lane < 2 * RB && j0 + (lane & 1) < n;
-    const unsigned idx = mine ? (unsigned)(lane >> 1) * (unsigned)n + (unsigned)(j0 + (lane & 1)) : 0u;
-    const unsigned total = (unsigned)RB * (unsigned)n;
     unsigned ld0[P], ld1[P];
+    bool mine = false;
+    unsigned idx = 0;
     // The epilogue's operands: asked for once the weights are on their way (pointer-table slots first, with
-    // scalar loads).  Always the same number of loads -- an operand that comes from a register slot is
-    // fetched from the GEMV's own output buffer instead and ignored -- so that every wait on the weights
-    // knows exactly how many younger loads are outstanding.
+    // scalar loads, all at once).  Always the same number of loads -- an operand that comes from a register
+    // slot is fetched from the GEMV's own output buffer instead and ignored -- so that every wait on the
+    // weights knows exactly how many younger loads are outstanding.
     auto fetch = [&] {
-        // read through the kernel-argument segment's address, made opaque here: otherwise the compiler moves
-        // these loads (invariant memory) back to the top of the kernel, in front of the weight loads
-        const GemvEpiArgs PG_CONSTANT* ka = (const GemvEpiArgs PG_CONSTANT*)__builtin_amdgcn_kernarg_segment_ptr();
-        asm volatile("" : "+s"(ka));
-        n_epi = ka->n_epi;
+        {   // the rest of the arguments, through the kernel-argument segment's address made opaque: otherwise the
+            // compiler moves these loads (invariant memory) to the top of the kernel, in front of the weight loads
+            const GemvEpiArgs PG_CONSTANT* kp = (const GemvEpiArgs PG_CONSTANT*)ka;
+            asm volatile("" : "+s"(kp));
+            eps = kp->eps;
 #pragma unroll
-        for (int i = 0; i < P; i++) {
-            a0[i] = ka->ph[i].in0; a1[i] = ka->ph[i].in1; outs[i] = static_cast<bf16_t*>(ka->ph[i].out);
-            ms[i] = ka->ph[i].m; metas[i] = ka->ph[i].meta; inds[i] = ka->ph[i].ind;
+            for (int i = 0; i < P; i++) {
+                a0[i] = kp->ph[i].in0; a1[i] = kp->ph[i].in1; outs[i] = static_cast<bf16_t*>(kp->ph[i].out);
+                ms[i] = kp->ph[i].m; metas[i] = kp->ph[i].meta; inds[i] = kp->ph[i].ind;
+            }
+            asm volatile("" : "+s"(eps),
+                              "+s"(a0[0]), "+s"(a1[0]), "+s"(outs[0]), "+s"(ms[0]), "+s"(metas[0]), "+s"(inds[0]),
+                              "+s"(a0[1]), "+s"(a1[1]), "+s"(outs[1]), "+s"(ms[1]), "+s"(metas[1]), "+s"(inds[1]),
+                              "+s"(a0[2]), "+s"(a1[2]), "+s"(outs[2]), "+s"(ms[2]), "+s"(metas[2]), "+s"(inds[2]));
         }
+        mine = lane < 2 * RB && j0 + (lane & 1) < n;
+        idx = mine ? (unsigned)(lane >> 1) * (unsigned)n + (unsigned)(j0 + (lane & 1)) : 0u;
+        const unsigned total = (unsigned)RB * (unsigned)n;
+        bool f0[P], f1[P], s0[P], s1[P];
+        unsigned any = 0;
 #pragma unroll
         for (int i = 0; i < P; i++) {
             const unsigned mt = metas[i];
-            const bool f0 = ((mt >> 8) & 0xffu) == kMergeFromMemory;
-            const bool f1 = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
-            const bf16_t* q0 = f0 ? static_cast<const bf16_t*>(resolve_rt(a0[i], inds[i] & 1)) : y;
-            const bf16_t* q1 = f1 ? static_cast<const bf16_t*>(resolve_rt(a1[i], inds[i] & 2)) : y;
-            const unsigned m = f1 ? ms[i] : total;
-            ld0[i] = load_raw_global(q0 + idx);
-            ld1[i] = load_raw_global(q1 + (m == total ? idx : idx % m));
+            f0[i] = ((mt >> 8) & 0xffu) == kMergeFromMemory;
+            f1[i] = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
+            s0[i] = f0[i] && (inds[i] & 1u);
+            s1[i] = f1[i] && (inds[i] & 2u);
+            any |= (f0[i] ? inds[i] & 1u : 0u) | (f1[i] ? inds[i] & 2u : 0u);
+        }
+        any = __builtin_amdgcn_readfirstlane(any);
+        asm volatile("" : "+s"(any));       // keeps what follows behind the weight loads
+        if (any) {
+            SlotPtr at0[P], at1[P];
+            const void* t0[P];
+            const void* t1[P];
+#pragma unroll
+            for (int i = 0; i < P; i++) { at0[i] = slot_addr(a0[i], s0[i]); at1[i] = slot_addr(a1[i], s1[i]); }
+#pragma unroll
+            for (int i = 0; i < P; i++) { t0[i] = *at0[i]; t1[i] = *at1[i]; }
+            asm volatile("" : "+s"(t0[0]), "+s"(t1[0]), "+s"(t0[1]), "+s"(t1[1]), "+s"(t0[2]), "+s"(t1[2]));
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                if (s0[i]) a0[i] = t0[i];
+                if (s1[i]) a1[i] = t1[i];
+            }
+        }
+        const bf16_t* q0[P];
+        const bf16_t* q1[P];
+        unsigned mm[P];
+        bool plain = true;      // no operand has a broadcast period: the usual case, one branch for all
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            q0[i] = f0[i] ? static_cast<const bf16_t*>(a0[i]) : y;
+            q1[i] = f1[i] ? static_cast<const bf16_t*>(a1[i]) : y;
+            mm[i] = f1[i] ? ms[i] : total;
+            plain = plain && mm[i] == total;
+        }
+        if (__builtin_expect(plain, 1)) {
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                ld0[i] = load_raw_global_at(q0[i], idx);
+                ld1[i] = load_raw_global_at(q1[i], idx);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                ld0[i] = load_raw_global_at(q0[i], idx);
+                ld1[i] = load_raw_global_at(q1[i], idx % mm[i]);
+            }
         }
     };
     float sums[2][RB];
-    if (aligned_to(W, 16) && aligned_to(h, 16) && (!PRO || aligned_to(gain, 16)))
-        gemv_sums_shared<bf16_t, 2, RB, true, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, p.eps, hstore, part);
+    if (__builtin_expect(aligned_to(W, 16) && aligned_to(h, 16) && (!PRO || aligned_to(gain, 16)), 1))
+        gemv_sums_shared<bf16_t, 2, RB, true, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, eps, hstore, part);
     else
-        gemv_sums_shared<bf16_t, 2, RB, false, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, p.eps, hstore, part);
+        gemv_sums_shared<bf16_t, 2, RB, false, true, PRO>(W, h, n, j0, lane, tid, hs, fetch, sums, gain, eps, hstore, part);
     float v = sums[0][0];
 #pragma unroll
     for (int rr = 0; rr < RB; rr++)
@@ -1315,6 +1399,10 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
         for (int r = 0; r < 2; r++)
             if (lane == rr * 2 + r) v = sums[r][rr];
     unsigned bits = f32_to_bf16(v);
+    // The epilogue's operands have been on their way since before the weights were used; claim them all now,
+    // before the first store of the tail.  Loads and stores complete in one queue, in order, so a wait for
+    // an operand placed after a store would wait for that store to be acknowledged as well.
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     if (mine && (head & kEpiHeadStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx) = (unsigned short)bits;
     float slot[kMergeSlots];
 #pragma unroll
@@ -1325,26 +1413,28 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
         for (int q = 0; q < kMergeSlots; q++)
             if (dst == (unsigned)q) slot[q] = from_raw<bf16_t>(bits);
     }
-#pragma unroll 1
-    for (int i = 0; i < n_epi; i++) {
-        unsigned mt = metas[0], ind = inds[0], ra = ld0[0], rb = ld1[0];
-        bf16_t* out = outs[0];
+    // Unrolled, with the one big choice (GELU or not) as the only branch inside a phase: a taken branch costs
+    // this one-wave-per-SIMD tail more than a dozen arithmetic instructions.
 #pragma unroll
-        for (int j = 1; j < P; j++)
-            if (i == j) { mt = metas[j]; ind = inds[j]; ra = ld0[j]; rb = ld1[j]; out = outs[j]; }
+    for (int i = 0; i < P; i++) {
+        if (i >= n_epi) break;
+        const unsigned mt = metas[i], ind = inds[i];
         const unsigned op = mt & 0xffu, src0 = (mt >> 8) & 0xffu, src1 = (mt >> 16) & 0xffu, dst = mt >> 24;
-        float fa = from_raw<bf16_t>(ra), fb = from_raw<bf16_t>(rb);
+        float fa = from_raw<bf16_t>(ld0[i]), fb = from_raw<bf16_t>(ld1[i]);
 #pragma unroll
         for (int q = 0; q < kMergeSlots; q++) {
             if (src0 == (unsigned)q) fa = slot[q];
             if (src1 == (unsigned)q) fb = slot[q];
         }
         float fo;
-        if (op == kAdd) fo = ew_apply<kAdd, false>(fa, fb);
-        else if (op == kMul) fo = ew_apply<kMul, false>(fa, fb);
-        else fo = ew_apply<kGelu, false>(fa, 0.f);
+        if (op == kGelu) {
+            fo = ew_apply<kGelu, false>(fa, 0.f);
+        } else {
+            const float sum = ew_apply<kAdd, false>(fa, fb), prod = ew_apply<kMul, false>(fa, fb);
+            fo = op == kAdd ? sum : prod;
+        }
         bits = f32_to_bf16(fo);
-        if (mine && (ind & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(out + idx) = (unsigned short)bits;
+        if (mine && (ind & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[i] + idx) = (unsigned short)bits;
 #pragma unroll
         for (int q = 0; q < kMergeSlots; q++)
             if (dst == (unsigned)q) slot[q] = from_raw<bf16_t>(bits);
