@@ -156,8 +156,12 @@ const void* table_kernel();
 // epilogue works element by element and takes any n).
 bool merge_candidate(int op, int dtype, const Shape& shape, bool whole_vectors, long long* n_out);
 const void* merged_kernel(int dtype);
-// Is this the GEMV shape k_gemv_shared<bf16, ., 2, rows> serves (the one the epilogue form exists for)?
+// Is this a GEMV shape an epilogue form exists for?  bf16, rows of 2048 columns: up to 4 rows of h (the
+// shape k_gemv_shared<bf16, ., 2, rows> serves; n >= 1024), or 5 rows and more (the matrix-core forms
+// plan() picks for such rows; n >= 32).  *n_out = rows * n.
 bool merge_head(int op, int dtype, const Shape& shape, long long* n_out);
+// The epilogue form for that many rows of h; launched with the grid and row groups plan() gives the plain
+// GEMV of the same shape.  A prologue exists up to 4 rows only (null otherwise).
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue);
 
 }  // namespace pgk

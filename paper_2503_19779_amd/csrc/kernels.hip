@@ -875,9 +875,126 @@ __device__ __forceinline__ void mm_mfma(const v4u* a, const v4u* b, f32x4& acc) 
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[i]), acc, 0, 0, 0);
 }
 
-// sum the 4 waves' partial tiles in a fixed order and store rows r0 .. r0 + 15 of the 16 columns at j0
-template <int NC = 16>
-__device__ __forceinline__ void mm_reduce_store(float* red, f32x4 acc, bf16_t* y, int rows, int n, int r0, int j0, int wave, int lane) {
+// What becomes of a finished tile.  All four waves share the output stage: a lane is given NE consecutive
+// rows of one column -- begin(r, j, ok) before the partial sums are exchanged (or earlier), put(k, v) for
+// each of its sums, end().
+// MmStore: the stand-alone kernels -- each sum is rounded and stored.
+template <int NE>
+struct MmStore {
+    bf16_t* y;
+    int rows, n;
+    size_t at = 0;
+    int r = 0;
+    bool col_ok = false;
+    __device__ __forceinline__ void begin(int r_, int j, bool ok) { r = r_; col_ok = ok; at = (size_t)r_ * n + j; }
+    __device__ __forceinline__ void put(int k, float v) { if (col_ok && r + k < rows) store_elem(y + at + (size_t)k * n, v); }
+    __device__ __forceinline__ void end() {}
+};
+// MmEpilogue: the kernels that follow the GEMV in the chain, element for element, ride along (kernels.h,
+// GemvEpiArgs): begin() asks for their operands, so that they arrive while the tile is multiplied and the
+// partial sums are exchanged; end() plays the kernels on the lane's outputs, rounding to bf16 after each as
+// the stand-alone kernels do, with the GELU as the only branch.
+template <int NE>
+struct MmEpilogue {
+    static constexpr int P = kEpiMaxPhases;
+    bf16_t* y;
+    int rows, n;
+    unsigned head;
+    int n_epi;
+    const bf16_t* q0[P];        // operand addresses, pointer-table slots resolved; null: comes from a register slot
+    const bf16_t* q1[P];
+    bf16_t* outs[P];
+    unsigned ms[P], metas[P], inds[P];
+    // per call
+    unsigned idx[NE];
+    bool ok[NE];
+    unsigned ld0[P][NE], ld1[P][NE];
+    float v[NE];
+    __device__ __forceinline__ void begin(int r, int j, bool col_ok) {
+        const unsigned total = (unsigned)rows * (unsigned)n;
+#pragma unroll
+        for (int e = 0; e < NE; e++) {
+            ok[e] = col_ok && r + e < rows;
+            idx[e] = ok[e] ? (unsigned)(r + e) * (unsigned)n + (unsigned)j : 0u;
+        }
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            if (i < n_epi && q0[i]) {
+#pragma unroll
+                for (int e = 0; e < NE; e++) ld0[i][e] = load_raw_global_at(q0[i], idx[e]);
+            }
+            if (i < n_epi && q1[i]) {
+                const unsigned m = ms[i];
+#pragma unroll
+                for (int e = 0; e < NE; e++) ld1[i][e] = load_raw_global_at(q1[i], m == total ? idx[e] : idx[e] % m);
+            }
+        }
+    }
+    __device__ __forceinline__ void put(int e, float sum) { v[e] = sum; }
+    __device__ __forceinline__ void end() {
+        unsigned bits[NE];
+        float slot[kMergeSlots][NE];
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): every operand, before the first store (see k_gemv_epilogue)
+#pragma unroll
+        for (int e = 0; e < NE; e++) {
+            bits[e] = f32_to_bf16(v[e]);
+            if (ok[e] && (head & kEpiHeadStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx[e]) = (unsigned short)bits[e];
+        }
+        {
+            const unsigned dst = (head >> 8) & 0xffu;
+#pragma unroll
+            for (int q = 0; q < kMergeSlots; q++)
+#pragma unroll
+                for (int e = 0; e < NE; e++) slot[q][e] = dst == (unsigned)q ? from_raw<bf16_t>(bits[e]) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            if (i >= n_epi) break;
+            const unsigned mt = metas[i], ind = inds[i];
+            const unsigned op = mt & 0xffu, src0 = (mt >> 8) & 0xffu, src1 = (mt >> 16) & 0xffu, dst = mt >> 24;
+            float fa[NE], fb[NE], fo[NE];
+#pragma unroll
+            for (int e = 0; e < NE; e++) {
+                fa[e] = from_raw<bf16_t>(ld0[i][e]);
+                fb[e] = from_raw<bf16_t>(ld1[i][e]);
+#pragma unroll
+                for (int q = 0; q < kMergeSlots; q++) {
+                    if (src0 == (unsigned)q) fa[e] = slot[q][e];
+                    if (src1 == (unsigned)q) fb[e] = slot[q][e];
+                }
+            }
+            if (op == kGelu) {
+#pragma unroll
+                for (int e = 0; e < NE; e++) fo[e] = ew_apply<kGelu, false>(fa[e], 0.f);
+            } else {
+#pragma unroll
+                for (int e = 0; e < NE; e++) {
+                    const float sum = ew_apply<kAdd, false>(fa[e], fb[e]), prod = ew_apply<kMul, false>(fa[e], fb[e]);
+                    fo[e] = op == kAdd ? sum : prod;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < NE; e++) {
+                bits[e] = f32_to_bf16(fo[e]);
+                if (ok[e] && (ind & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[i] + idx[e]) = (unsigned short)bits[e];
+#pragma unroll
+                for (int q = 0; q < kMergeSlots; q++)
+                    if (dst == (unsigned)q) slot[q][e] = from_raw<bf16_t>(bits[e]);
+            }
+        }
+    }
+};
+
+// where the output stage of the 16-column forms puts a lane: wave w takes row w of the four that an
+// accumulator lane holds
+template <int NC = 16, class Emit>
+__device__ __forceinline__ void mm_emit_begin(Emit& emit, int n, int r0, int j0, int wave, int lane) {
+    emit.begin(r0 + (lane >> 4) * 4 + wave, j0 + (lane & 15), j0 + (lane & 15) < n && (NC == 16 || (lane & 15) < NC));
+}
+// sum the 4 waves' partial tiles in a fixed order and hand rows r0 .. r0 + 15 of the 16 columns at j0 to `emit`
+// (mm_emit_begin has been called for this tile)
+template <class Emit>
+__device__ __forceinline__ void mm_reduce_store(float* red, f32x4 acc, Emit& emit, int wave, int lane) {
     // A matrix-core result may not be read by an LDS write until the instruction has drained (up to
     // 19 wait states for the longest forms).  The compiler inserts those itself inside a block, but
     // it was seen to omit them when the last multiply of a K loop and this write sit in different
@@ -887,21 +1004,18 @@ __device__ __forceinline__ void mm_reduce_store(float* red, f32x4 acc, bf16_t* y
     float* dst = red + ((size_t)wave * 64 + lane) * 4;
     dst[0] = acc.x; dst[1] = acc.y; dst[2] = acc.z; dst[3] = acc.w;
     __syncthreads();
-    if (wave == 0) {
-        const int j = j0 + (lane & 15);
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const float p0 = red[((size_t)0 * 64 + lane) * 4 + e], p1 = red[((size_t)1 * 64 + lane) * 4 + e];
-            const float p2 = red[((size_t)2 * 64 + lane) * 4 + e], p3 = red[((size_t)3 * 64 + lane) * 4 + e];
-            const int r = r0 + (lane >> 4) * 4 + e;
-            if (r < rows && j < n && (NC == 16 || (lane & 15) < NC)) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
-        }
+    {
+        const int e = wave;
+        const float p0 = red[((size_t)0 * 64 + lane) * 4 + e], p1 = red[((size_t)1 * 64 + lane) * 4 + e];
+        const float p2 = red[((size_t)2 * 64 + lane) * 4 + e], p3 = red[((size_t)3 * 64 + lane) * 4 + e];
+        emit.put(0, ((p0 + p1) + p2) + p3);
     }
     __syncthreads();      // `red` is free again
+    emit.end();
 }
 
-template <bool FULL, bool SINGLE, bool AL>
-__device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols, int row_groups,
+template <bool FULL, bool SINGLE, bool AL, class Emit>
+__device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols, int row_groups,
                                                char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
@@ -931,8 +1045,9 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
         mm_read_frags(lds, lane, b);
         mm_zero_tail<FULL>(b, cols, 0, wave, kq);
         __builtin_amdgcn_sched_barrier(0);   // all fragment reads before the first multiply, not one LDS latency per pair
+        mm_emit_begin(emit, n, t0 * 16, j0, wave, lane);
         mm_mfma(a, b, acc);
-        mm_reduce_store(red, acc, y, rows, n, t0 * 16, j0, wave, lane);
+        mm_reduce_store(red, acc, emit, wave, lane);
 #pragma unroll 1
         for (int t = t0 + 1; t < t1; t++) {
             acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -941,8 +1056,9 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
             mm_read_frags(lds, lane, a);
             mm_zero_tail<FULL>(a, cols, 0, wave, kq);
             __builtin_amdgcn_sched_barrier(0);
+            mm_emit_begin(emit, n, t * 16, j0, wave, lane);
             mm_mfma(a, b, acc);
-            mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
+            mm_reduce_store(red, acc, emit, wave, lane);
         }
     } else {
 #pragma unroll 1
@@ -961,7 +1077,8 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
                 __builtin_amdgcn_sched_barrier(0);
                 mm_mfma(a, b, acc);
             }
-            mm_reduce_store(red, acc, y, rows, n, t * 16, j0, wave, lane);
+            mm_emit_begin(emit, n, t * 16, j0, wave, lane);
+            mm_reduce_store(red, acc, emit, wave, lane);
         }
     }
 }
@@ -973,8 +1090,8 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
 // slot held before and their results are never stored.  NRH = 8 (4) when rows <= 8 (4): the absent
 // rows of the tile are not loaded either.  With two tiles of rows (8 columns x 2 tiles = 512
 // workgroups, measured) it loses to the 16-column form: 5.7 against 4.9 us at 32 rows.
-template <bool FULL, bool AL, int NRH>
-__device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols,
+template <bool FULL, bool AL, int NRH, class Emit>
+__device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols,
                                                       char* stage, float* red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
@@ -992,8 +1109,9 @@ __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf1
     mm_read_frags(lds, lane, b);
     mm_zero_tail<FULL>(b, cols, 0, wave, kq);
     __builtin_amdgcn_sched_barrier(0);
+    mm_emit_begin<8>(emit, n, r0, j0, wave, lane);
     mm_mfma(a, b, acc);
-    mm_reduce_store<8>(red, acc, y, rows, n, r0, j0, wave, lane);
+    mm_reduce_store(red, acc, emit, wave, lane);
 }
 
 template <int IND, bool FULL, int NRH>
@@ -1001,19 +1119,20 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16_narrow(GemvArgs p)
     const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
     const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
     bf16_t* y = static_cast<bf16_t*>(p.out);
+    MmStore<1> emit{y, p.rows, p.n};
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);
-    if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<FULL, true, NRH>(W, h, y, p.rows, p.n, p.cols, stage, red);
-    else gemm_mfma_narrow_body<FULL, false, NRH>(W, h, y, p.rows, p.n, p.cols, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<FULL, true, NRH>(W, h, emit, p.rows, p.n, p.cols, stage, red);
+    else gemm_mfma_narrow_body<FULL, false, NRH>(W, h, emit, p.rows, p.n, p.cols, stage, red);
 }
 
 // Wide form for many rows and cols == 2048: 32 output columns per workgroup, i.e. two sets of weight
 // fragments and two accumulators against every staged tile of h, which halves the h traffic per
 // output (the bound once rows >= 64).  One workgroup per CU (the fragments of 32 columns do not fit
 // the register budget of two), waves 0 and 1 each finish one 16-column half.
-template <bool AL>
-__device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_t* h, bf16_t* y, int rows, int n, int cols, int row_groups,
+template <bool AL, class Emit>
+__device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols, int row_groups,
                                                     char* stage, float* red /* LDS: [2 halves][4 waves][64 lanes][4] */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ncb = (n + 31) / 32;
@@ -1038,6 +1157,8 @@ __device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_
     for (int t = t0;;) {
         f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         __builtin_amdgcn_sched_barrier(0);
+        // output stage: wave w finishes rows 2 * (w >> 1), + 1 of each accumulator lane's four, in 16-column half w & 1
+        emit.begin(t * 16 + (lane >> 4) * 4 + (wave >> 1) * 2, j0 + (wave & 1) * 16 + (lane & 15), j0 + (wave & 1) * 16 + (lane & 15) < n);
 #pragma unroll
         for (int i = 0; i < kMmSteps; i++) {
             acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b0[i]), acc0, 0, 0, 0);
@@ -1049,18 +1170,18 @@ __device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_
         d0[0] = acc0.x; d0[1] = acc0.y; d0[2] = acc0.z; d0[3] = acc0.w;
         d1[0] = acc1.x; d1[1] = acc1.y; d1[2] = acc1.z; d1[3] = acc1.w;
         __syncthreads();
-        if (wave < 2) {
-            const float* src = red + (size_t)wave * 4 * 64 * 4;
-            const int j = j0 + wave * 16 + (lane & 15);
+        {
+            const float* src = red + (size_t)(wave & 1) * 4 * 64 * 4;
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
+            for (int k = 0; k < 2; k++) {
+                const int e = (wave >> 1) * 2 + k;
                 const float p0 = src[((size_t)0 * 64 + lane) * 4 + e], p1 = src[((size_t)1 * 64 + lane) * 4 + e];
                 const float p2 = src[((size_t)2 * 64 + lane) * 4 + e], p3 = src[((size_t)3 * 64 + lane) * 4 + e];
-                const int r = t * 16 + (lane >> 4) * 4 + e;
-                if (r < rows && j < n) store_elem(y + (size_t)r * n + j, ((p0 + p1) + p2) + p3);
+                emit.put(k, ((p0 + p1) + p2) + p3);
             }
         }
         __syncthreads();
+        emit.end();
         if (++t >= t1) break;
         mm_stage(lds, lane, g);
         if (t + 1 < t1) mm_load_rows<true, AL>(h, rows, cols, (t + 1) * 16, 0, wave, lane, g);
@@ -1073,11 +1194,12 @@ __global__ __launch_bounds__(kBlock, 1) void k_gemm_mfma_bf16_wide(GemvArgs p) {
     const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
     const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
     bf16_t* y = static_cast<bf16_t*>(p.out);
+    MmStore<2> emit{y, p.rows, p.n};
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[2 * 4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);
-    if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
-    else gemm_mfma_wide_body<false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, emit, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    else gemm_mfma_wide_body<false>(W, h, emit, p.rows, p.n, p.cols, p.row_groups, stage, red);
 }
 
 template <int IND, bool FULL, bool SINGLE>
@@ -1085,11 +1207,61 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
     const bf16_t* W = static_cast<const bf16_t*>(resolve<(IND & 1) != 0>(p.W));
     const bf16_t* h = static_cast<const bf16_t*>(resolve<(IND & 2) != 0>(p.h));
     bf16_t* y = static_cast<bf16_t*>(p.out);
+    MmStore<1> emit{y, p.rows, p.n};
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[4 * 64 * 4];
     const bool al = aligned_to(W, 16) && aligned_to(h, 16);   // rows keep the alignment: cols is a multiple of 8
-    if (__builtin_expect(al, 1)) gemm_mfma_body<FULL, SINGLE, true>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
-    else gemm_mfma_body<FULL, SINGLE, false>(W, h, y, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    if (__builtin_expect(al, 1)) gemm_mfma_body<FULL, SINGLE, true>(W, h, emit, p.rows, p.n, p.cols, p.row_groups, stage, red);
+    else gemm_mfma_body<FULL, SINGLE, false>(W, h, emit, p.rows, p.n, p.cols, p.row_groups, stage, red);
+}
+
+// The matrix-core forms with an elementwise epilogue (kernels.h, GemvEpiArgs; no prologue): the same bodies,
+// with MmEpilogue in place of the plain store.  Only for rows of 2048 columns.  FORM 0: narrow, 8 rows of h
+// loaded; 1: narrow, 16; 2: 16 columns per workgroup, one pass over K; 3: wide.
+template <int NE>
+__device__ __forceinline__ void mm_epilogue_setup(const GemvEpiArgs& p, MmEpilogue<NE>& e) {
+    e.y = static_cast<bf16_t*>(p.g.out);
+    e.rows = p.g.rows;
+    e.n = p.g.n;
+    e.head = p.head;
+    e.n_epi = p.n_epi;
+#pragma unroll
+    for (int i = 0; i < MmEpilogue<NE>::P; i++) {
+        const unsigned mt = p.ph[i].meta, ind = p.ph[i].ind;
+        const bool f0 = ((mt >> 8) & 0xffu) == kMergeFromMemory;
+        const bool f1 = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
+        e.q0[i] = f0 ? static_cast<const bf16_t*>(resolve_rt(p.ph[i].in0, ind & 1u)) : nullptr;
+        e.q1[i] = f1 ? static_cast<const bf16_t*>(resolve_rt(p.ph[i].in1, ind & 2u)) : nullptr;
+        e.outs[i] = static_cast<bf16_t*>(p.ph[i].out);
+        e.ms[i] = p.ph[i].m;
+        e.metas[i] = mt;
+        e.inds[i] = ind;
+#pragma unroll
+        for (int k = 0; k < NE; k++) e.ld0[i][k] = e.ld1[i][k] = 0u;
+    }
+}
+template <int FORM>
+__global__ __launch_bounds__(kBlock, FORM == 3 ? 1 : 2) void k_gemm_mfma_epilogue(GemvEpiArgs p) {
+    const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, p.head & 1u));
+    const bf16_t* h = static_cast<const bf16_t*>(resolve_rt(p.g.h, p.head & 2u));
+    __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
+    __shared__ float red[(FORM == 3 ? 2 : 1) * 4 * 64 * 4];
+    MmEpilogue<FORM == 3 ? 2 : 1> emit;
+    mm_epilogue_setup(p, emit);
+    const bool al = aligned_to(W, 16) && aligned_to(h, 16);
+    if constexpr (FORM == 0) {
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 8>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+        else gemm_mfma_narrow_body<true, false, 8>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+    } else if constexpr (FORM == 1) {
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+        else gemm_mfma_narrow_body<true, false, 16>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+    } else if constexpr (FORM == 2) {
+        if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+        else gemm_mfma_body<true, true, false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+    } else {
+        if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+        else gemm_mfma_wide_body<false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+    }
 }
 
 // ---- merged dispatches ------------------------------------------------------------------------------
@@ -1777,14 +1949,27 @@ bool merge_candidate(int op, int dtype, const Shape& s, bool whole_vectors, long
 }
 
 bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
-    // exactly the shapes plan_gemv gives to k_gemv_shared<bf16, IND, 2, rows>
-    if (op != kGemv || dtype != kBF16) return false;
-    if (s.rows < 1 || s.rows > 4 || s.n < 1024 || s.cols != 64 * kGemvChunk * 8) return false;
+    if (op != kGemv || dtype != kBF16 || s.cols != 64 * kGemvChunk * 8 || s.rows < 1) return false;
+    if (s.rows <= 4) {
+        // exactly the shapes plan_gemv gives to k_gemv_shared<bf16, IND, 2, rows>
+        if (s.n < 1024) return false;
+    } else {
+        // the matrix-core forms plan_gemv picks for rows of 2048 columns: narrow (up to 16 rows), 16 columns per
+        // workgroup, wide (from kMmWideRows rows); element indices are kept in 32 bits
+        if (s.n < 32 || s.rows * s.n > (1ll << 31)) return false;
+    }
     *n_out = s.rows * s.n;
     return true;
 }
 
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue) {
+    if (rows_of_h > 4) {
+        if (with_prologue) return nullptr;
+        if (rows_of_h <= 8) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<0>);
+        if (rows_of_h <= 16) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<1>);
+        if (rows_of_h < kMmWideRows) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<2>);
+        return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<3>);
+    }
     switch (rows_of_h * 2 + (with_prologue ? 1 : 0)) {
     case 2: return reinterpret_cast<const void*>(&k_gemv_epilogue<1, false>);
     case 3: return reinterpret_cast<const void*>(&k_gemv_epilogue<1, true>);
