@@ -645,17 +645,23 @@ __device__ __forceinline__ void gemv_sums_shared(const T* W, const T* h, int n, 
     if constexpr (PRO) {
         float fg[NV];
         Vec<T, 16>::unpack(wg, fg);
+        // every row's sum of squares first, then one barrier for all rows (a row of partial sums per row of x)
 #pragma unroll
         for (int rr = 0; rr < RB; rr++) {
-            float fx[NV], fo[NV];
+            float fx[NV];
             Vec<T, 16>::unpack(hv[rr], fx);
             float acc = 0.f;
 #pragma unroll
             for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fx[e], fx[e], acc);
             acc = wave_sum(acc);
-            float* prow = part + rr * (kBlock / 64);               // a row of partial sums per row of x: one barrier each
-            if ((tid & 63) == 0) prow[tid >> 6] = acc;
-            lds_barrier();
+            if ((tid & 63) == 0) part[rr * (kBlock / 64) + (tid >> 6)] = acc;
+        }
+        lds_barrier();
+#pragma unroll
+        for (int rr = 0; rr < RB; rr++) {
+            float fx[NV], fo[NV];
+            Vec<T, 16>::unpack(hv[rr], fx);
+            const float* prow = part + rr * (kBlock / 64);
             const float total = ((prow[0] + prow[1]) + prow[2]) + prow[3];
             const float scale = 1.0f / sqrtf(total / (float)kCols + eps);
 #pragma unroll
