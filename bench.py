@@ -71,6 +71,9 @@ def main() -> int:
                     help="skip the legs added beside the three modes (host-side node updates, per-tensor memcpy, the two alternating table "
                          "mechanisms, the event-timed medians).  They are skipped by themselves when a profiler is attached: two counter-collection "
                          "runs that included them did not complete (one went silent, one ended in a segmentation fault inside a profiler thread)")
+    ap.add_argument("--no-gemv-graphs", action="store_true",
+                    help="skip the graphs of the dominant kernel alone (they build, capture and destroy two more chains).  For counter-collection "
+                         "runs, which only need the kernels of the main chain: one such run went silent inside these legs")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--profile-iters", type=int, default=20, help="samples per (segment, mode) of the slow-path profiler")
     args = ap.parse_args()
@@ -191,27 +194,38 @@ def main() -> int:
         log(f"[bench] dispatch floor: {graph_node_us:.2f} us per graph node, {eager_launch_us:.2f} us per eager launch")
 
     # ------------------------------------------------------------------ the dominant kernel alone, HIP events on the launch stream
-    # In graph replay the dominant kernel is the GEMV 2048x2048 with its epilogue (GELU of the result and the
-    # residual add ride in its dispatch); in eager launches it is the plain GEMV.  Each is timed in a graph of
-    # the chain's 120 such launches and nothing else (same kernels, same launch shapes, the chain's own 120
-    # weight matrices, input vector fixed): events around R replays give the time per launch.  It includes
-    # the dispatch gap between two dependent launches, so it is an upper bound of the kernel's own duration
-    # (the rocprofv3 kernel trace gives the latter).
+    # In graph replay the dominant kernel is the decode sub-block's one dispatch: the GEMV 2048x2048 with the
+    # RMSNorm in front of it as its prologue and the GELU and the residual add behind it as its epilogue; in
+    # eager launches it is the plain GEMV.  Each is timed in a graph of the chain's 120 such launches (same
+    # kernels, same launch shapes, the chain's own 120 weight matrices, the stream initialised by one small
+    # add): events around R replays give the time per launch.  It includes the dispatch gap between two
+    # dependent launches, so it is an upper bound of the kernel's own duration (the rocprofv3 kernel trace
+    # gives the latter).
     from pg_workloads import INT
     n_gemv = sum(1 for k in spec.kernels if k.op == "gemv")
     H = spec.meta["hidden"]
     reps = 50
 
-    def gemv_graph_us(with_epilogue: bool) -> float:
+    def gemv_graph_us(sub_block: bool):
+        """(us per launch, launches per replay) of a graph of the chain's GEMVs alone, or of its whole sub-blocks."""
+        X, T1, T2 = 0, 1, 2
+        gain = n_gemv + 1
         ks = []
+        if sub_block:
+            ks.append(KernelSpec("add", "bf16", X, (Ref(WEIGHT, n_gemv), Ref(WEIGHT, n_gemv)), H, m=H))       # the stream, before the first sub-block
         for s_ in range(n_gemv):
-            ks.append(KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s_), Ref(WEIGHT, n_gemv)), H, rows=1, cols=H))
-            if with_epilogue:
-                ks.append(KernelSpec("gelu", "bf16", 0, (Ref(INT, 0),), H))
-                ks.append(KernelSpec("add", "bf16", 1, (Ref(INT, 1) if s_ else Ref(WEIGHT, n_gemv), Ref(INT, 0)), H, m=H))
-        gspec = ChainSpec("gemv_only", ks, [], [TensorSpec("bf16", H), TensorSpec("bf16", H)], list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H)], [0])
-        gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0]], dev)
-        assert gchain.graph_dispatches()[0] == n_gemv
+            if sub_block:
+                ks.append(KernelSpec("rmsnorm", "bf16", T1, (Ref(INT, X), Ref(WEIGHT, gain)), H, rows=1, cols=H, eps=1e-6))
+                ks.append(KernelSpec("gemv", "bf16", T2, (Ref(WEIGHT, s_), Ref(INT, T1)), H, rows=1, cols=H))
+                ks.append(KernelSpec("gelu", "bf16", T2, (Ref(INT, T2),), H))
+                ks.append(KernelSpec("add", "bf16", X, (Ref(INT, X), Ref(INT, T2)), H, m=H))
+            else:
+                ks.append(KernelSpec("gemv", "bf16", 0, (Ref(WEIGHT, s_), Ref(WEIGHT, n_gemv)), H, rows=1, cols=H))
+        gspec = ChainSpec("gemv_only", ks, [], [TensorSpec("bf16", H)] * 3,
+                          list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H), TensorSpec("bf16", H)], [0])
+        gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0], w_dev[n_gemv]], dev)
+        nodes = gchain.graph_dispatches()[0]
+        assert nodes == n_gemv + (1 if sub_block else 0), nodes      # an even number of sub-blocks: none is split (see DESIGN, renaming)
         gchain.capture(stream)
         for _ in range(5):
             gchain.replay_copy([], stream)
@@ -222,21 +236,26 @@ def main() -> int:
         e1.record(stream)
         e1.synchronize()
         gchain.close()
-        return e0.elapsed_time(e1) * 1e3 / (reps * n_gemv)
+        return e0.elapsed_time(e1) * 1e3 / (reps * nodes), nodes
 
-    gemv_us = gemv_graph_us(False)
-    epi_us = gemv_graph_us(True)
+    if args.no_gemv_graphs:       # the figures that need them are then reported as NaN
+        gemv_us = epi_us = float("nan")
+        epi_nodes = n_gemv + 1
+    else:
+        gemv_us, _ = gemv_graph_us(False)
+        epi_us, epi_nodes = gemv_graph_us(True)
     gemv_bytes = H * H * 2 + H * 2 + H * 2       # bf16 weight matrix + input vector + output vector
-    epi_bytes = H * H * 2 + H * 2 + H * 2 + 2 * H * 2    # + the residual stream read, and the GELU result and the new stream written
-    log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s; with GELU + residual add as its epilogue: {epi_us:.2f} us = {epi_bytes / epi_us / 1e3:.0f} GB/s")
+    # weight matrix; read: the stream and the gain; written: the normalised vector, the GELU result, the new stream
+    epi_bytes = H * H * 2 + 2 * H * 2 + 3 * H * 2
+    log(f"[bench] GEMV alone: {gemv_us:.2f} us per launch = {gemv_bytes / gemv_us / 1e3:.0f} GB/s; the whole sub-block (RMSNorm, GEMV, GELU, residual add) in one dispatch: {epi_us:.2f} us = {epi_bytes / epi_us / 1e3:.0f} GB/s")
     tr = profile_figures("decode_chain_b1_kernel_trace.md")
     hb = profile_figures("gemv_and_copy_kernel_hbm_traffic.md")
-    how = ("HIP events on the launch stream around 50 replays of a graph of the chain's 120 launches of this kernel; "
-           "the time per launch includes the dispatch gap between two dependent launches")
-    roofline = {"kernel": "k_gemv_epilogue<1>: bf16 GEMV 2048x2048, batch 1, with GELU and the residual add as its epilogue (one graph node; the dominant kernel of graph replay)",
+    how = ("HIP events on the launch stream around 50 replays of a graph of the chain's 120 launches of this kernel (and one small add that "
+           "initialises the stream, counted as a launch); the time per launch includes the dispatch gap between two dependent launches")
+    roofline = {"kernel": "k_gemv_epilogue<1, prologue>: bf16 GEMV 2048x2048, batch 1, with the RMSNorm as its prologue and GELU and the residual add as its epilogue (a decode sub-block in one graph node; the dominant kernel of graph replay)",
                 "bound": "hbm", "achieved": epi_bytes / epi_us / 1e3, "peak": HBM_PEAK, "unit": "GB/s", "frac": epi_bytes / epi_us / 1e3 / HBM_PEAK,
                 "frac_denominator": "avg_launch_us: " + how,
-                "bytes_per_launch": epi_bytes, "avg_launch_us": epi_us, "launches_timed": reps * n_gemv,
+                "bytes_per_launch": epi_bytes, "avg_launch_us": epi_us, "launches_timed": reps * epi_nodes,
                 # the same bytes over the kernel's own duration in the committed rocprofv3 kernel trace (dispatch start to end, mean over all its dispatches)
                 "profile_kernel_mean_us": tr.get("gemv_epilogue_kernel_mean_us"),
                 "frac_from_profile": (epi_bytes / tr["gemv_epilogue_kernel_mean_us"] / 1e3 / HBM_PEAK) if tr.get("gemv_epilogue_kernel_mean_us") else None,

@@ -264,12 +264,16 @@ pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */
  * each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
  * results stay bit-identical to eager launches.  A run ends where a kernel reads something an earlier
  * kernel of the run wrote in any other pattern than element for element.  Likewise up to 3 elementwise
- * kernels over the outputs of a bf16 GEMV with up to 4 rows of h (GELU of the result, the residual add,
- * an input add) ride in the GEMV's dispatch as an epilogue: each lane that holds a finished output
- * rounds it as the GEMV's store would and runs the following kernels on that element.  Outputs that a
- * later kernel of the same run overwrites are not stored (nothing could read them in between).  Eager
- * launches are never merged.  `on` = 0 captures one node per kernel.  Takes effect at the next
- * pg_capture. */
+ * kernels over the outputs of a bf16 GEMV over rows of 2048 columns (GELU of the result, the residual
+ * add, an input add) ride in the GEMV's dispatch as an epilogue: each lane that holds a finished output
+ * rounds it as the GEMV's store would and runs the following kernels on that element.  Up to 4 rows of
+ * h the RMSNorm that produces the GEMV's input rides in front of it as a prologue (every workgroup
+ * normalises the rows itself, one stores them); a run whose epilogue overwrites the buffer its prologue
+ * reads writes a second copy of that buffer, which the workspace holds (pg_chain_workspace_bytes counts
+ * it), and every segment ends with all internal buffers in their first copy, where pg_chain_int_buffer
+ * and the other modes find them.  Outputs that a later kernel of the same run overwrites are not
+ * stored (nothing could read them in between).  Eager launches are never merged.  `on` = 0 captures
+ * one node per kernel.  Takes effect at the next pg_capture. */
 pg_status pg_set_dispatch_merge(pg_chain *chain, int32_t on);
 /* Kernel nodes that the graphs of one replay hold with merging on (*merged_out) and off
  * (*unmerged_out = the number of kernels).  Either output may be NULL.  Host only. */

@@ -303,25 +303,24 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
         if (d.op == PG_ADD || d.op == PG_MUL) return j == 0 || (d.m ? d.m : d.n) == n;
         return j == 0;                                                  // GELU a, RMSNORM x
     };
+    // Is kernel i an RMSNorm [rows <= 4, 2048] straight into a GEMV of the epilogue kernel's shape (its prologue)?
+    auto prologue_at = [&](int i) {
+        if (!(k[i].op == PG_RMSNORM && k[i].dtype == PG_BF16 && i + 1 < k1 && k[i].rows >= 1 && k[i].rows <= 4)) return false;
+        const pg_kernel_desc& v = k[i + 1];
+        long long nv = 0;
+        if (!(pgk::merge_head(v.op, v.dtype, shape_of(v), &nv) && k[i].cols == v.cols && k[i].rows == v.rows &&
+              v.in[1].kind == PG_REF_INT && v.in[1].index == k[i].out.index &&
+              !(v.in[0].kind == PG_REF_INT && v.in[0].index == k[i].out.index))) return false;
+        // the GEMV itself may overwrite x: renamed like an epilogue kernel's write, if it covers the buffer
+        const pg_ref& x = k[i].in[0];
+        return !(x.kind == PG_REF_INT && v.out.index == x.index && ints[x.index].numel != nv);
+    };
     int i = k0;
     while (i < k1) {
         MergeGroup g;
         g.k0 = i;
         long long n = 0;
-        // RMSNorm [rows, 2048] straight into a GEMV of the epilogue kernel's shape?
-        bool pro = false;
-        if (k[i].op == PG_RMSNORM && k[i].dtype == PG_BF16 && i + 1 < k1 && k[i].rows >= 1 && k[i].rows <= 4) {
-            const pg_kernel_desc& v = k[i + 1];
-            long long nv = 0;
-            pro = pgk::merge_head(v.op, v.dtype, shape_of(v), &nv) && k[i].cols == v.cols && k[i].rows == v.rows &&
-                  v.in[1].kind == PG_REF_INT && v.in[1].index == k[i].out.index &&
-                  !(v.in[0].kind == PG_REF_INT && v.in[0].index == k[i].out.index);
-            if (pro) {
-                // the GEMV itself may overwrite x: renamed like an epilogue kernel's write, if it covers the buffer
-                const pg_ref& x = k[i].in[0];
-                if (x.kind == PG_REF_INT && v.out.index == x.index && ints[x.index].numel != nv) pro = false;
-            }
-        }
+        const bool pro = prologue_at(i);
         const int hk = i + (pro ? 1 : 0);
         const bool head = pro || pgk::merge_head(k[i].op, k[i].dtype, shape_of(k[i]), &n);
         if (!head && !pgk::merge_candidate(k[i].op, k[i].dtype, shape_of(k[i]), true, &n)) {
@@ -365,6 +364,7 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
             long long ni = 0;
             if (!pgk::merge_candidate(d.op, d.dtype, shape_of(d), !head, &ni) || ni != n || d.dtype != k[g.k0].dtype) break;
             if (head && d.op == PG_RMSNORM) break;                       // a row-wide reduction cannot ride in a wave's epilogue
+            if (!head && prologue_at(i)) break;                          // left to the GEMV behind it, where it costs next to nothing
             const int nin = n_inputs(d.op);
             unsigned char src[2] = {(unsigned char)pgk::kMergeFromMemory, (unsigned char)pgk::kMergeFromMemory};
             bool ok = true;
