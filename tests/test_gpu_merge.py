@@ -151,7 +151,8 @@ def test_prologue_hazards(rows):
     h.close()
 
 
-@pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100)])
+@pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100),
+                                    (5, 1027), (8, 2048), (13, 1030), (16, 40), (17, 1100), (40, 1029), (63, 48), (64, 1030), (100, 2048), (130, 70)])
 def test_gemv_with_elementwise_epilogue(rows, n):
     """A GEMV (ragged last workgroup for odd n) followed by GELU in place, an add with an external operand,
     a mul with a broadcast weight and further kernels: the first three ride in the GEMV's dispatch, the rest
@@ -177,7 +178,8 @@ def test_gemv_with_elementwise_epilogue(rows, n):
     h = Harness(spec, capture=False)
     merged, unmerged = h.chain.graph_dispatches()
     say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
-    # [gemv gelu add mul] [add] [add] [gemv mul] [add]; the two adds in the middle merge too when they have the same element count
+    # [gemv gelu add mul] [add] [add] [gemv mul] [add]; the two adds in the middle merge too when they have the same
+    # element count (a whole number of vectors); below 1024 columns of output the one-to-four-row GEMV has no epilogue form
     assert unmerged == 9 and merged == (4 if n == H else 5), merged
     h.chain.capture(h.stream)
     for t in range(4):
