@@ -415,6 +415,7 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
             np++;
             i++;
         }
+        if (i == g.k0) i++;      // the first kernel itself was refused (only a descriptor that validation rejects gets here): on its own
         g.k1 = i;
         // an output is stored unless a later kernel of the run overwrites the same buffer (nothing reads memory in between)
         for (int a = 0; a < np; a++) {
@@ -1075,9 +1076,14 @@ pg_status pg_chain_workspace_bytes(const pg_kernel_desc* kernels, int32_t nk, co
         if (n_inputs(kernels[i].op) < 0) return fail(PG_EINVAL, "kernel %d: bad op", i);
         if (i == 0 ? kernels[i].segment != 0 : (kernels[i].segment != kernels[i - 1].segment && kernels[i].segment != kernels[i - 1].segment + 1))
             return fail(PG_EINVAL, "kernel %d: bad segment order", i);
-        for (int j = 0; j < 3; j++)
+        if (kernels[i].out.kind != PG_REF_INT || kernels[i].out.index < 0 || kernels[i].out.index >= n_int)
+            return fail(PG_EINVAL, "kernel %d: output must be an internal buffer in range", i);
+        for (int j = 0; j < 3; j++) {
             if (kernels[i].in[j].kind == PG_REF_EXT && (kernels[i].in[j].index < 0 || kernels[i].in[j].index >= n_ext))
                 return fail(PG_EINVAL, "kernel %d: external reference out of range", i);
+            if (kernels[i].in[j].kind == PG_REF_INT && (kernels[i].in[j].index < 0 || kernels[i].in[j].index >= n_int))
+                return fail(PG_EINVAL, "kernel %d: internal reference out of range", i);
+        }
     }
     for (int i = 0; i < n_ext; i++) if (ext[i].numel <= 0 || ext[i].numel > (1ll << 40) || (ext[i].dtype != PG_F32 && ext[i].dtype != PG_BF16)) return fail(PG_EINVAL, "ext %d: bad descriptor", i);
     for (int i = 0; i < n_int; i++) if (ints[i].numel <= 0 || ints[i].numel > (1ll << 40) || (ints[i].dtype != PG_F32 && ints[i].dtype != PG_BF16)) return fail(PG_EINVAL, "int %d: bad descriptor", i);

@@ -174,6 +174,24 @@ def test_malformed_descriptors_are_rejected(name):
     assert "kernel" in str(e.value) or "segment" in str(e.value)
 
 
+@pytest.mark.timeout(30)
+def test_size_query_of_a_descriptor_that_validation_rejects_returns():
+    """The workspace-size query lays the chain out, planner of merged dispatches included, before the full
+    validation of pg_chain_build has run: a kernel whose output is also its broadcast operand (or its RMSNorm
+    gain) must come back as an error or a size, at once -- the planner refuses such a kernel as the first of a
+    run and must still move on."""
+    H = 2048
+    for bad in (KernelSpec("rmsnorm", "bf16", 0, (Ref(EXT, 0), Ref(INT, 0)), H, rows=1, cols=H, eps=1e-6),
+                KernelSpec("add", "bf16", 0, (Ref(EXT, 0), Ref(INT, 0)), H, m=8),
+                KernelSpec("mul", "f32", 0, (Ref(EXT, 0), Ref(INT, 0)), H, m=1)):
+        dt = bad.dtype
+        first = KernelSpec("add", dt, 0, (Ref(EXT, 0), Ref(EXT, 0)), H, m=H)
+        spec = ChainSpec("bad", [first, bad, first], [TensorSpec(dt, H)], [TensorSpec(dt, H)], [], [0])
+        with pytest.raises(pg.PgError) as e:
+            pg.Chain.host_only(spec)
+        assert e.value.status == 1 and "kernel 1" in str(e.value)
+
+
 def test_wellformed_variants_are_accepted():
     s = _base()
     pg.Chain.host_only(s).close()
