@@ -303,9 +303,9 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
         if (d.op == PG_ADD || d.op == PG_MUL) return j == 0 || (d.m ? d.m : d.n) == n;
         return j == 0;                                                  // GELU a, RMSNORM x
     };
-    // Is kernel i an RMSNorm [rows <= 4, 2048] straight into a GEMV of the epilogue kernel's shape (its prologue)?
+    // Is kernel i an RMSNorm [few rows, 2048] straight into a GEMV of the epilogue kernel's shape (its prologue)?
     auto prologue_at = [&](int i) {
-        if (!(k[i].op == PG_RMSNORM && k[i].dtype == PG_BF16 && i + 1 < k1 && k[i].rows >= 1 && k[i].rows <= 4)) return false;
+        if (!(k[i].op == PG_RMSNORM && k[i].dtype == PG_BF16 && i + 1 < k1 && k[i].rows >= 1 && k[i].rows <= pgk::kPrologueMaxRows)) return false;
         const pg_kernel_desc& v = k[i + 1];
         long long nv = 0;
         if (!(pgk::merge_head(v.op, v.dtype, shape_of(v), &nv) && k[i].cols == v.cols && k[i].rows == v.rows &&

@@ -161,7 +161,8 @@ const void* merged_kernel(int dtype);
 // plan() picks for such rows; n >= 32).  *n_out = rows * n.
 bool merge_head(int op, int dtype, const Shape& shape, long long* n_out);
 // The epilogue form for that many rows of h; launched with the grid and row groups plan() gives the plain
-// GEMV of the same shape.  A prologue exists up to 4 rows only (null otherwise).
+// GEMV of the same shape.  A prologue exists up to kPrologueMaxRows rows (null otherwise).
+constexpr int kPrologueMaxRows = 16;
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue);
 
 }  // namespace pgk

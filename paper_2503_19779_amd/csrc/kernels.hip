@@ -1096,18 +1096,84 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
 // slot held before and their results are never stored.  NRH = 8 (4) when rows <= 8 (4): the absent
 // rows of the tile are not loaded either.  With two tiles of rows (8 columns x 2 tiles = 512
 // workgroups, measured) it loses to the 16-column form: 5.7 against 4.9 us at 32 rows.
-template <bool FULL, bool AL, int NRH, class Emit>
+// RMSNorm of the rows the narrow form has just loaded, as a prologue (FULL, 2048 columns): lane (wave, l)
+// holds 16-byte chunk c of every row, where c runs over all 256 chunks of a row across the workgroup, but
+// not in lane order.  The stand-alone kernel's sums must be reproduced bit for bit: per chunk the fused
+// sum of squares in element order (any lane can do that), then the chunk sums travel through LDS to the
+// lane the stand-alone kernel would have had them in (lane t <-> chunk t), where wave_sum and the fixed
+// order of the four wave sums follow; lane r < NRH turns row r's total into its scale, and every lane
+// scales its own chunks: (x * scale) * gain, one rounding.  `scratch`: NRH * 256 + NRH * 4 + NRH floats of
+// LDS that nothing else uses until the rows are staged.  hstore: this workgroup also stores the rows.
+template <int NRH>
+__device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned* wg /* the lane's chunk of the gain */, float eps, bf16_t* hstore,
+                                                int rows, int wave, int lane, float* scratch) {
+    constexpr int kCols = 32 * 4 * kMmSteps;
+    const int tid = wave * 64 + lane;
+    const int k0 = mm_k0(0, wave, lane);
+    float* sq = scratch;                       // [NRH][256]: chunk sums, indexed by chunk (bits 3-4 swizzled with bits 5-6: the lanes of
+                                               // a wave hold chunks 32 apart, which would all fall into the same eight banks)
+    float* part = scratch + NRH * 256;         // [NRH][4]: wave sums
+    float* scale = part + NRH * 4;             // [NRH]
+    auto at = [](int c) { return c ^ (((c >> 5) & 3) << 3); };
+    float fx[NRH][8];
+#pragma unroll
+    for (int r = 0; r < NRH; r++) {
+        Vec<bf16_t, 16>::unpack(g[r], fx[r]);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc = __builtin_fmaf(fx[r][e], fx[r][e], acc);
+        sq[r * 256 + at(k0 >> 3)] = acc;
+    }
+    lds_barrier();
+#pragma unroll
+    for (int r = 0; r < NRH; r++) {
+        const float acc = wave_sum(sq[r * 256 + at(tid)]);
+        if (lane == 0) part[r * 4 + wave] = acc;
+    }
+    lds_barrier();
+    if (tid < NRH) {
+        const float* prow = part + tid * 4;
+        const float total = ((prow[0] + prow[1]) + prow[2]) + prow[3];
+        scale[tid] = 1.0f / sqrtf(total / (float)kCols + eps);
+    }
+    lds_barrier();
+    float fg[8];
+    Vec<bf16_t, 16>::unpack(wg, fg);
+#pragma unroll
+    for (int r = 0; r < NRH; r++) {
+        float fo[8];
+        const float sc = scale[r];
+#pragma unroll
+        for (int e = 0; e < 8; e++) fo[e] = (fx[r][e] * sc) * fg[e];
+        Vec<bf16_t, 16>::pack(fo, g[r]);
+    }
+    if (hstore) {
+#pragma unroll
+        for (int r = 0; r < NRH; r++)
+            if (r < rows) store_vec_global(hstore + (size_t)r * kCols + k0, g[r]);
+    }
+}
+
+template <bool FULL, bool AL, int NRH, bool PRO = false, class Emit>
 __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols,
-                                                      char* stage, float* red) {
+                                                      char* stage, float* red, const bf16_t* gain = nullptr, float eps = 0.f, bf16_t* hstore = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
     const int j0 = blockIdx.x * 8, r0 = 0;
     char* lds = stage + wave * kMmWaveLds;
     unsigned g[NRH][4], gw[8][4];
     v4u a[kMmSteps], b[kMmSteps];
-    mm_load_rows<FULL, AL, NRH>(h, rows, cols, r0, 0, wave, lane, g);
+    mm_load_rows<FULL, AL, NRH>(h, rows, cols, r0, 0, wave, lane, g);      // with a prologue: the rows to normalise
+    unsigned wg[4] = {0u, 0u, 0u, 0u};
+    if constexpr (PRO) load_vec_global<bf16_t, AL, false>(gain + mm_k0(0, wave, lane), wg);   // before the weights: loads come back in order
     mm_load_rows<FULL, AL, 8>(W, n, cols, j0, 0, wave, lane, gw);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (PRO) {
+        static_assert(FULL, "the prologue exists for rows of 2048 columns");
+        static_assert((NRH * 256 + NRH * 5) * sizeof(float) <= 4 * kMmWaveLds, "the prologue's sums fit the staging area");
+        mm_rmsnorm_rows<NRH>(g, wg, eps, hstore, rows, wave, lane, reinterpret_cast<float*>(stage));
+        lds_barrier();        // the sums are read: the staging area takes the rows now
+    }
     mm_stage<NRH>(lds, lane, g);
     mm_read_frags(lds, lane, a);
     mm_zero_tail<FULL>(a, cols, 0, wave, kq);
@@ -1246,21 +1312,25 @@ __device__ __forceinline__ void mm_epilogue_setup(const GemvEpiArgs& p, MmEpilog
         for (int k = 0; k < NE; k++) e.ld0[i][k] = e.ld1[i][k] = 0u;
     }
 }
-template <int FORM>
-__global__ __launch_bounds__(kBlock, FORM == 3 ? 1 : 2) void k_gemm_mfma_epilogue(GemvEpiArgs p) {
+template <int FORM, bool PRO = false>
+__global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfma_epilogue(GemvEpiArgs p) {
+    static_assert(!PRO || FORM <= 1, "a prologue exists for the narrow forms only");
     const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, p.head & 1u));
-    const bf16_t* h = static_cast<const bf16_t*>(resolve_rt(p.g.h, p.head & 2u));
+    // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where workgroup 0 stores it
+    const bf16_t* h = static_cast<const bf16_t*>(PRO ? resolve_rt(p.x, p.head & kEpiXSlot) : resolve_rt(p.g.h, p.head & 2u));
+    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(resolve_rt(p.gain, p.head & kEpiGainSlot)) : nullptr;
+    bf16_t* hstore = (PRO && (p.head & kEpiStoreH) && blockIdx.x == 0) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[(FORM == 3 ? 2 : 1) * 4 * 64 * 4];
     MmEpilogue<FORM == 3 ? 2 : 1> emit;
     mm_epilogue_setup(p, emit);
-    const bool al = aligned_to(W, 16) && aligned_to(h, 16);
+    const bool al = aligned_to(W, 16) && aligned_to(h, 16) && (!PRO || aligned_to(gain, 16));
     if constexpr (FORM == 0) {
-        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 8>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
-        else gemm_mfma_narrow_body<true, false, 8>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 8, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
+        else gemm_mfma_narrow_body<true, false, 8, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
     } else if constexpr (FORM == 1) {
-        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
-        else gemm_mfma_narrow_body<true, false, 16>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red);
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
+        else gemm_mfma_narrow_body<true, false, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
     } else if constexpr (FORM == 2) {
         if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
         else gemm_mfma_body<true, true, false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
@@ -1970,7 +2040,11 @@ bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
 
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue) {
     if (rows_of_h > 4) {
-        if (with_prologue) return nullptr;
+        if (with_prologue) {
+            if (rows_of_h <= 8) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<0, true>);
+            if (rows_of_h <= 16) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<1, true>);
+            return nullptr;
+        }
         if (rows_of_h <= 8) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<0>);
         if (rows_of_h <= 16) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<1>);
         if (rows_of_h < kMmWideRows) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<2>);
