@@ -1350,8 +1350,9 @@ __global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfm
 // need static indices; a lane beyond the tensor re-reads the last vector and never stores, so there is
 // no per-lane branch and all fetches are in flight together), then ONE copy of the arithmetic in a loop
 // over the kernels that picks its operands out of the fetched vectors and the register slots with
-// conditional moves.  Code size counts: the kernel runs once per dispatch on a CU whose instruction
-// cache has most likely never seen it, so every 64 bytes on the executed path are a fetch from memory.
+// conditional moves (one copy of the GELU and of the RMSNorm reduction for up to four kernels; an
+// unrolled form with every operand choice resolved at run time by branches was slower: a taken branch
+// costs a one-wave-per-SIMD kernel about as much as a dozen arithmetic instructions).
 
 template <typename T, bool AL>
 __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const* in0, const T* const* in1, float* part) {
