@@ -258,10 +258,11 @@ pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */
 /* Dispatch merging at capture (on by default).  A graph is "one dispatch, the GPU launches the rest"
  * (Sec. 2.2); on this machine every dependent kernel node still costs about 1.5 us of dispatch, so a
  * captured graph, which knows the whole chain, plays a run of up to 4 consecutive kernels with ONE
- * dispatch where it can: add / mul / GELU (bf16; fp32 except GELU) and RMSNorm over rows of 256 x 16
- * bytes, all element for element over the same n elements (a whole number of 16-byte vectors).  A
- * lane runs the kernels in order on its 16 bytes with their stand-alone arithmetic and one rounding
- * each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
+ * dispatch where it can: add / mul / GELU and RMSNorm over rows of 256 x 16 bytes, all element for
+ * element over the same n elements (a whole number of 16-byte vectors; fp32 tensors of up to 16384
+ * elements are worked one element per lane instead, with any n, and only there the fp32 GELU takes
+ * part).  A lane runs the kernels in order on its elements with their stand-alone arithmetic and one
+ * rounding each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
  * results stay bit-identical to eager launches.  A run ends where a kernel reads something an earlier
  * kernel of the run wrote in any other pattern than element for element.  Likewise up to 3 elementwise
  * kernels over the outputs of a bf16 GEMV over rows of 2048 columns (GELU of the result, the residual

@@ -87,6 +87,7 @@ struct MergeGroup {
     bool head = false;               // the run is a GEMV's dispatch: the kernels after the GEMV ride in it as an epilogue
     bool pro = false;                // (head) kernel k0 is the RMSNorm that feeds the GEMV k0 + 1, and rides in front of it as a prologue
     int rename = -1;                 // (pro) internal buffer the RMSNorm reads and the run overwrites: the run writes its other copy
+    bool narrow = false;             // (not head) one 4-byte element per lane instead of a 16-byte vector
     long long n = 0;                 // elements every kernel of the run produces
     int gemv() const { return k0 + (pro ? 1 : 0); }
     // per kernel of the run: where its operands come from (a register slot or memory), which slot keeps its
@@ -332,6 +333,9 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
         g.n = n;
         g.head = head;
         g.pro = pro;
+        // a run of small fp32 kernels works one element per lane (no RMSNorm in it); decided by its first kernel
+        const bool narrow = !head && k[i].op != PG_RMSNORM && pgk::merge_narrow(k[i].dtype, n);
+        g.narrow = narrow;
         int held[pgk::kMergeSlots];                  // internal buffer whose current contents a slot holds, or -1
         for (int& h : held) h = -1;
         std::vector<int> written, broadcast_read;    // internal buffers the run has written / read other than element for element
@@ -364,6 +368,7 @@ void plan_groups(const pg_kernel_desc* k, int k0, int k1, const pg_tensor_desc* 
             long long ni = 0;
             if (!pgk::merge_candidate(d.op, d.dtype, shape_of(d), !head, &ni) || ni != n || d.dtype != k[g.k0].dtype) break;
             if (head && d.op == PG_RMSNORM) break;                       // a row-wide reduction cannot ride in a wave's epilogue
+            if (!head && narrow != (d.op != PG_RMSNORM && pgk::merge_narrow(d.dtype, ni))) break;   // one lane width per run
             if (!head && prologue_at(i)) break;                          // left to the GEMV behind it, where it costs next to nothing
             const int nin = n_inputs(d.op);
             unsigned char src[2] = {(unsigned char)pgk::kMergeFromMemory, (unsigned char)pgk::kMergeFromMemory};
@@ -585,9 +590,9 @@ pg_status make_records(pg_chain* c) {
                 g.launch.grid = c->rec[g.gemv()].direct.grid;               // the GEMV's own launch shape: same workgroups, same lanes
                 if (c->rec[g.gemv()].direct.block.x != 256) return fail(PG_EINVAL, "kernel %d: unexpected GEMV launch shape", g.gemv());
             } else {
-                g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype);
+                g.launch.fn = pgk::merged_kernel(c->k[g.k0].dtype, g.narrow);
                 g.launch.arg_bytes = sizeof(pgk::MergedArgs);
-                const long long nvec = g.n / (c->k[g.k0].dtype == PG_F32 ? 4 : 8);
+                const long long nvec = g.narrow ? g.n : g.n / (c->k[g.k0].dtype == PG_F32 ? 4 : 8);
                 g.launch.grid = dim3((unsigned)((nvec + 255) / 256));       // one workgroup per unit of 256 lanes x 16 bytes
             }
             if (!g.launch.fn) return fail(PG_EINVAL, "kernel %d: no merged kernel for this run", g.k0);

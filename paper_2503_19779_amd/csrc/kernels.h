@@ -155,7 +155,13 @@ const void* table_kernel();
 // whole_vectors: n must be a whole number of 16-byte vectors (runs of one workgroup per unit; a GEMV's
 // epilogue works element by element and takes any n).
 bool merge_candidate(int op, int dtype, const Shape& shape, bool whole_vectors, long long* n_out);
-const void* merged_kernel(int dtype);
+// Runs over small fp32 tensors work one element (4 bytes) per lane instead of a 16-byte vector: such
+// kernels are bound by their dispatch, not by bytes, and one element per lane is what lets the fp32 GELU
+// (evaluated in fp64, a few hundred instructions) ride along.  No RMSNorm in such a run (its row is a unit
+// of 256 lanes x 16 bytes).
+constexpr long long kMergeNarrowMax = 16384;        // elements
+bool merge_narrow(int dtype, long long n);
+const void* merged_kernel(int dtype, bool narrow);
 // Is this a GEMV shape an epilogue form exists for?  bf16, rows of 2048 columns: up to 4 rows of h (the
 // shape k_gemv_shared<bf16, ., 2, rows> serves; n >= 1024), or 5 rows and more (the matrix-core forms
 // plan() picks for such rows; n >= 32).  *n_out = rows * n.

@@ -143,6 +143,15 @@ __device__ __forceinline__ void load_vec_global(const T* p, unsigned* w) {
         for (int i = 0; i < 4; i++) w[i] = (unsigned)q[2 * i] | ((unsigned)q[2 * i + 1] << 16);
     }
 }
+// The 4-byte vector (one fp32 or two bf16 elements) through a global pointer.
+template <typename T, bool AL>
+__device__ __forceinline__ void load_vec4_global(const T* p, unsigned* w) {
+    if constexpr (sizeof(T) == 4 || AL) w[0] = *(const unsigned PG_GLOBAL*)(uintptr_t)p;
+    else {
+        const unsigned short PG_GLOBAL* q = (const unsigned short PG_GLOBAL*)(uintptr_t)p;
+        w[0] = (unsigned)q[0] | ((unsigned)q[1] << 16);
+    }
+}
 template <typename T>
 __device__ __forceinline__ unsigned load_raw_global(const T* p) {
     if constexpr (sizeof(T) == 4) return *(const unsigned PG_GLOBAL*)(uintptr_t)p;
@@ -1354,10 +1363,14 @@ __global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfm
 // unrolled form with every operand choice resolved at run time by branches was slower: a taken branch
 // costs a one-wave-per-SIMD kernel about as much as a dozen arithmetic instructions).
 
-template <typename T, bool AL>
+template <typename T, int VB, bool AL>
 __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const* in0, const T* const* in1, float* part) {
-    using V = Vec<T, 16>;
-    constexpr int NV = V::NV;
+    using V = Vec<T, VB>;
+    constexpr int NV = V::NV, NW = VB / 4;
+    auto fetch = [](const T* q, unsigned* w) {
+        if constexpr (VB == 16) load_vec_global<T, AL>(q, w);
+        else load_vec4_global<T, AL>(q, w);
+    };
     constexpr bool kWide = sizeof(T) == 4;
     constexpr int P = kMergeMaxPhases;
     const unsigned tid = threadIdx.x;
@@ -1375,24 +1388,24 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
     const unsigned v = blockIdx.x * kBlock + tid;
     const bool act = v < nvec;
     const unsigned i0 = (act ? v : nvec - 1) * NV;
-    unsigned ld0[P][4], ld1[P][4];
+    unsigned ld0[P][NW], ld1[P][NW];
 #pragma unroll
     for (int i = 0; i < P; i++) {
         const unsigned mt = metas[i], op = mt & 0xffu;
         if (((mt >> 8) & 0xffu) == kMergeFromMemory) {
-            load_vec_global<T, AL>(in0[i] + i0, ld0[i]);
+            fetch(in0[i] + i0, ld0[i]);
         } else {
 #pragma unroll
-            for (int k = 0; k < 4; k++) ld0[i][k] = 0u;
+            for (int k = 0; k < NW; k++) ld0[i][k] = 0u;
         }
         if (op != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory) {
             const unsigned m = p.ph[i].m;
             if (op == kRmsNorm || m % NV == 0) {
                 // RMSNorm: a row is one unit, lane t holds vector t of the gain; add / mul: a vector of b never wraps around the period
-                load_vec_global<T, AL>(in1[i] + (op == kRmsNorm ? tid * NV : (m == n ? i0 : i0 % m)), ld1[i]);
+                fetch(in1[i] + (op == kRmsNorm ? tid * NV : (m == n ? i0 : i0 % m)), ld1[i]);
             } else {
 #pragma unroll
-                for (int k = 0; k < 4; k++) ld1[i][k] = 0u;
+                for (int k = 0; k < NW; k++) ld1[i][k] = 0u;
 #pragma unroll
                 for (int e = 0; e < NV; e++) {                     // the raw bits, element by element
                     const unsigned r = load_raw_global(in1[i] + (i0 + e) % m);
@@ -1402,14 +1415,14 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
             }
         } else {
 #pragma unroll
-            for (int k = 0; k < 4; k++) ld1[i][k] = 0u;
+            for (int k = 0; k < NW; k++) ld1[i][k] = 0u;
         }
     }
-    unsigned slot[kMergeSlots][4];
+    unsigned slot[kMergeSlots][NW];
 #pragma unroll
     for (int q = 0; q < kMergeSlots; q++)
 #pragma unroll
-        for (int k = 0; k < 4; k++) slot[q][k] = 0u;
+        for (int k = 0; k < NW; k++) slot[q][k] = 0u;
     const int n_phase = p.n_phase;
     // All fetches have been asked for together; wait for them here, once.  Left to the compiler, the wait
     // sits at the head of the loop below and then also waits, every time round, for the store of the
@@ -1421,30 +1434,30 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
         T* out = outs[0];
         unsigned mt = metas[0];
         float eps = epss[0];
-        unsigned wa[4], wb[4], wo[4];
+        unsigned wa[NW], wb[NW], wo[NW];
 #pragma unroll
-        for (int k = 0; k < 4; k++) { wa[k] = ld0[0][k]; wb[k] = ld1[0][k]; }
+        for (int k = 0; k < NW; k++) { wa[k] = ld0[0][k]; wb[k] = ld1[0][k]; }
 #pragma unroll
         for (int j = 1; j < P; j++)
             if (i == j) {
                 out = outs[j]; mt = metas[j]; eps = epss[j];
 #pragma unroll
-                for (int k = 0; k < 4; k++) { wa[k] = ld0[j][k]; wb[k] = ld1[j][k]; }
+                for (int k = 0; k < NW; k++) { wa[k] = ld0[j][k]; wb[k] = ld1[j][k]; }
             }
         const unsigned op = mt & 0xffu, src0 = (mt >> 8) & 0xffu, src1 = (mt >> 16) & 0xffu, dst = mt >> 24;
 #pragma unroll
         for (int q = 0; q < kMergeSlots; q++) {
             if (src0 == (unsigned)q)
 #pragma unroll
-                for (int k = 0; k < 4; k++) wa[k] = slot[q][k];
+                for (int k = 0; k < NW; k++) wa[k] = slot[q][k];
             if (src1 == (unsigned)q)
 #pragma unroll
-                for (int k = 0; k < 4; k++) wb[k] = slot[q][k];
+                for (int k = 0; k < NW; k++) wb[k] = slot[q][k];
         }
         float fa[NV], fb[NV], fo[NV];
         V::unpack(wa, fa);
         V::unpack(wb, fb);
-        if (op == kRmsNorm) {
+        if (VB == 16 && op == kRmsNorm) {      // a row is one unit of 256 lanes x 16 bytes: never in the narrow form
             float acc = 0.f;
 #pragma unroll
             for (int e = 0; e < NV; e++) acc = __builtin_fmaf(fa[e], fa[e], acc);
@@ -1463,25 +1476,28 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
 #pragma unroll
             for (int e = 0; e < NV; e++) fo[e] = ew_apply<kMul, kWide>(fa[e], fb[e]);
         } else {
-            if constexpr (!kWide) {                                // fp32 GELU (evaluated in fp64) is never merged
+            if constexpr (!kWide || VB == 4) {                     // fp32 GELU (evaluated in fp64): one element per lane only
 #pragma unroll
-                for (int e = 0; e < NV; e++) fo[e] = ew_apply<kGelu, false>(fa[e], 0.f);
+                for (int e = 0; e < NV; e++) fo[e] = ew_apply<kGelu, kWide>(fa[e], 0.f);
             } else {
 #pragma unroll
                 for (int e = 0; e < NV; e++) fo[e] = fa[e];
             }
         }
         V::pack(fo, wo);
-        if (act) store_vec_global(out + i0, wo);
+        if (act) {
+            if constexpr (VB == 16) store_vec_global(out + i0, wo);
+            else *(unsigned PG_GLOBAL*)(uintptr_t)(out + i0) = wo[0];
+        }
 #pragma unroll
         for (int q = 0; q < kMergeSlots; q++)
             if (dst == (unsigned)q)
 #pragma unroll
-                for (int k = 0; k < 4; k++) slot[q][k] = wo[k];
+                for (int k = 0; k < NW; k++) slot[q][k] = wo[k];
     }
 }
 
-template <typename T>
+template <typename T, int VB>
 __global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
     constexpr int P = kMergeMaxPhases;
     __shared__ float part[kBlock / 64];
@@ -1495,15 +1511,15 @@ __global__ __launch_bounds__(kBlock) void k_merged(MergedArgs p) {
         const unsigned mt = p.ph[i].meta;
         if (((mt >> 8) & 0xffu) == kMergeFromMemory) {
             in0[i] = static_cast<const T*>(resolve_rt(p.ph[i].in0, p.ph[i].ind & 1));
-            al = al && aligned_to(in0[i], 16);
+            al = al && aligned_to(in0[i], VB);
         }
         if ((mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory) {
             in1[i] = static_cast<const T*>(resolve_rt(p.ph[i].in1, p.ph[i].ind & 2));
-            al = al && aligned_to(in1[i], 16);
+            al = al && aligned_to(in1[i], VB);
         }
     }
-    if (__builtin_expect(al, 1)) merged_body<T, true>(p, in0, in1, part);
-    else merged_body<T, false>(p, in0, in1, part);
+    if (__builtin_expect(al, 1)) merged_body<T, VB, true>(p, in0, in1, part);
+    else merged_body<T, VB, false>(p, in0, in1, part);
 }
 
 // GEMV with an elementwise epilogue: k_gemv_shared's body, then lane e of each wave plays output e through
@@ -2011,19 +2027,22 @@ bool merge_candidate(int op, int dtype, const Shape& s, bool whole_vectors, long
     const int nv = dtype == kF32 ? 4 : 8;
     long long n = 0;
     if (op == kAdd || op == kMul || op == kGelu) {
-        if (op == kGelu && dtype == kF32) return false;   // evaluated in fp64: too slow on one workgroup to be worth merging
         if (s.m <= 0) return false;
         n = s.n;
+        // fp32 GELU is evaluated in fp64: mergeable only where the run works one element per lane (small tensors)
+        if (op == kGelu && dtype == kF32 && !merge_narrow(dtype, n)) return false;
     } else if (op == kRmsNorm) {
         if (s.cols != (long long)kBlock * nv) return false;   // a row must be exactly one unit
         n = s.rows * s.cols;
     } else {
         return false;
     }
-    if (n <= 0 || (whole_vectors && n % nv != 0) || n > (1ll << 31)) return false;
+    if (n <= 0 || (whole_vectors && !merge_narrow(dtype, n) && n % nv != 0) || n > (1ll << 31)) return false;
     *n_out = n;
     return true;
 }
+
+bool merge_narrow(int dtype, long long n) { return dtype == kF32 && n > 0 && n <= kMergeNarrowMax; }
 
 bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
     if (op != kGemv || dtype != kBF16 || s.cols != 64 * kGemvChunk * 8 || s.rows < 1) return false;
@@ -2064,9 +2083,9 @@ const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue) {
     }
 }
 
-const void* merged_kernel(int dtype) {
-    if (dtype == kF32) return reinterpret_cast<const void*>(&k_merged<float>);
-    if (dtype == kBF16) return reinterpret_cast<const void*>(&k_merged<bf16_t>);
+const void* merged_kernel(int dtype, bool narrow) {
+    if (dtype == kF32) return narrow ? reinterpret_cast<const void*>(&k_merged<float, 4>) : reinterpret_cast<const void*>(&k_merged<float, 16>);
+    if (dtype == kBF16 && !narrow) return reinterpret_cast<const void*>(&k_merged<bf16_t, 16>);
     return nullptr;
 }
 

@@ -267,13 +267,31 @@ def test_runs_with_external_broadcast_and_evicted_operands(dtype, rows):
     h.close()
 
 
+@pytest.mark.parametrize("n_kernels,numel,nodes", [(9, 7, 3), (13, 16384, 4), (30, 16385, 30), (30, 20000, 20), (12, 1 << 20, 8)])
+def test_runs_of_small_and_large_fp32_kernels(n_kernels, numel, nodes):
+    """fp32 runs on small tensors (up to 16384 elements) work one element per lane and take the GELU along, four
+    kernels per dispatch; larger ones work in 16-byte vectors (a whole number of them) and leave the GELU, which is
+    evaluated in fp64, a dispatch of its own."""
+    spec = elementwise_chain(n_kernels=n_kernels, numel=numel)
+    h = Harness(spec, capture=False)
+    assert h.chain.graph_dispatches() == (nodes, n_kernels)
+    h.chain.capture(h.stream)
+    for t in range(3):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        assert same_bits(outs["eager"][0], outs["copy"][0]) and same_bits(outs["eager"][0], outs["indirect"][0])
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
+    h.close()
+
+
 def test_runs_of_elementwise_kernels():
-    """Config 1: add and mul on 4096 fp32 elements merge pairwise into single-workgroup dispatches, the
-    fp32 GELU between them stays a kernel of its own; bf16 chains of small kernels merge four at a time."""
+    """Config 1: add, mul and GELU on 4096 fp32 elements merge four at a time into dispatches of one element per
+    lane; bf16 chains of small kernels merge four at a time in 16-byte vectors."""
     spec = elementwise_chain()
     h = Harness(spec, capture=False)
     merged, unmerged = h.chain.graph_dispatches()
-    assert unmerged == 64 and merged == 43, merged
+    assert unmerged == 64 and merged == 16, merged
     h.chain.capture(h.stream)
     for t in range(3):
         x_np, x_dev = h.inputs(t)
