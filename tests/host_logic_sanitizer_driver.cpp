@@ -132,6 +132,40 @@ Chain random_chain(Rng& r) {
     return c;
 }
 
+// fp32 elementwise chains of every size class (one element per lane up to 16384 elements, 16-byte vectors above,
+// no merging when n is not a whole number of vectors), now and then with an RMSNorm over rows of 1024
+Chain random_fp32_chain(Rng& r) {
+    Chain c;
+    const long long sizes[] = {1, 7, 1024, 4096, 16384, 16385, 16388, 20000, 3 * 1024, 1 << 20};
+    const long long N = sizes[r.below(10)];
+    const int n_int = 1 + r.below(3);
+    for (int i = 0; i < n_int; i++) c.ints.push_back(pg_tensor_desc{PG_F32, 0, N});
+    c.ext.push_back(pg_tensor_desc{PG_F32, 0, N});
+    c.ext.push_back(pg_tensor_desc{PG_F32, 0, N});
+    c.w.push_back(pg_tensor_desc{PG_F32, 0, 1024});
+    std::vector<bool> full(n_int, false);
+    const int nk = 1 + r.below(20);
+    int seg = 0;
+    for (int i = 0; i < nk; i++) {
+        if (i && r.below(11) == 0) seg++;
+        const int out = r.below(n_int);
+        int src = r.below(n_int);
+        pg_ref a = full[src] ? ref(PG_REF_INT, src) : ref(PG_REF_EXT, r.below(2));
+        const int what = r.below(8);
+        if (what == 0 && N % 1024 == 0 && !(a.kind == PG_REF_INT && a.index == out)) {
+            c.k.push_back(kernel(PG_RMSNORM, PG_F32, seg, out, a, ref(PG_REF_WEIGHT, 0), kNone, 1024, 0, N / 1024, 1024, 0, 1e-5f));
+        } else if (what < 3) {
+            c.k.push_back(kernel(PG_GELU, PG_F32, seg, out, a, kNone, kNone, N, 0, 1, 0, 0, 0.f));
+        } else {
+            pg_ref b = r.below(2) ? ref(PG_REF_EXT, r.below(2)) : ref(PG_REF_WEIGHT, 0);
+            const long long m = b.kind == PG_REF_WEIGHT ? 1 + r.below(1024) : N;
+            c.k.push_back(kernel(r.below(2) ? PG_ADD : PG_MUL, PG_F32, seg, out, a, b, kNone, N, m, 1, 0, 0, 0.f));
+        }
+        full[out] = true;
+    }
+    return c;
+}
+
 int failures = 0;
 #define CHECK(cond) do { if (!(cond)) { std::printf("check failed at line %d: %s\n", __LINE__, #cond); failures++; } } while (0)
 
@@ -179,6 +213,7 @@ int main() {
     Rng r{20250317ull};
     int built = 0, total = 6000;
     for (int i = 0; i < total; i++) built += drive(random_chain(r), false) ? 1 : 0;
+    for (int i = 0; i < 2000; i++) CHECK(drive(random_fp32_chain(r), true));
     std::printf("random descriptors: %d of %d accepted\n", built, total);
     CHECK(built > total / 2 && built < total);
     // the selector: strict '<' scan in mode order
