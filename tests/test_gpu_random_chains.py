@@ -119,3 +119,106 @@ def test_random_chain(seed):
             assert same_bits(h.chain.output(o), b), ("stepping through", t)
         say(f"{spec.name}: iteration {t} step by step worst error / tolerance = {worst:.3f}")
     h.close()
+
+
+def random_decoder_like_chain(seed: int) -> ChainSpec:
+    """Rows of 2048 bf16 columns, the shape the merged GEMV dispatches exist for: RMSNorm often straight into a
+    GEMV, often followed by GELU and an add that overwrites the normalised stream (renaming), in-place and
+    out-of-place elementwise kernels, gains and broadcast operands, buffers larger than what a run rewrites,
+    segment cuts anywhere."""
+    rng = np.random.Generator(np.random.PCG64(7700 + seed))
+    H = 2048
+    rows = int(rng.choice([1, 2, 3, 4, 5, 8, 11, 16, 17, 40]))
+    N = rows * H
+    n_ext, n_int = int(rng.integers(1, 4)), int(rng.integers(3, 6))
+    big = int(rng.integers(n_int)) if rng.random() < 0.3 else -1           # one buffer twice the size the kernels write
+    weights = [TensorSpec("bf16", H * H, ("normal", 0.0, 1.0 / np.sqrt(H))), TensorSpec("bf16", H, ("normal", 1.0, 0.1)),
+               TensorSpec("bf16", N, ("normal", 0.0, 0.5))]
+    W_MAT, W_GAIN, W_FULL = 0, 1, 2
+    written = set()
+    ks, seg = [], 0
+
+    def source():
+        opts = [Ref(EXT, int(rng.integers(n_ext))), Ref(WEIGHT, W_FULL)] + [Ref(INT, i) for i in written] * 2
+        return opts[int(rng.integers(len(opts)))]
+
+    while len(ks) < int(rng.integers(6, 16)):
+        if ks and rng.random() < 0.12:
+            seg += 1
+        out = int(rng.integers(n_int))
+        what = rng.random()
+        if what < 0.3:
+            a = source()
+            b = source() if rng.random() < 0.6 else Ref(WEIGHT, W_GAIN)
+            m = int(rng.choice([H, 5])) if b == Ref(WEIGHT, W_GAIN) else N
+            o = a.index if (a.kind == INT and rng.random() < 0.5) else out
+            if b.kind == INT and b.index == o:
+                b = Ref(WEIGHT, W_FULL)
+            ks.append(KernelSpec(str(rng.choice(["add", "mul"])), "bf16", o, (a, b), N, seg, m=m))
+            written.add(o)
+        elif what < 0.45:
+            a = source()
+            o = a.index if (a.kind == INT and rng.random() < 0.5) else out
+            ks.append(KernelSpec("gelu", "bf16", o, (a,), N, seg))
+            written.add(o)
+        else:
+            x = source()
+            t1 = out if not (x.kind == INT and x.index == out) else (out + 1) % n_int
+            ks.append(KernelSpec("rmsnorm", "bf16", t1, (x, Ref(WEIGHT, W_GAIN)), H, seg, rows=rows, cols=H, eps=1e-5))
+            written.add(t1)
+            if rng.random() < 0.8:
+                t2 = int(rng.integers(n_int))
+                if t2 == t1:
+                    t2 = (t2 + 1) % n_int
+                ks.append(KernelSpec("gemv", "bf16", t2, (Ref(WEIGHT, W_MAT), Ref(INT, t1)), H, seg, rows=rows, cols=H))
+                written.add(t2)
+                if rng.random() < 0.6:
+                    ks.append(KernelSpec("gelu", "bf16", t2, (Ref(INT, t2),), N, seg))
+                if rng.random() < 0.6 and x.kind == INT and x.index != t2:
+                    ks.append(KernelSpec("add", "bf16", x.index, (x, Ref(INT, t2)), N, seg, m=N))
+                if rng.random() < 0.3:
+                    ks.append(KernelSpec("add", "bf16", t2, (Ref(INT, t2), Ref(EXT, int(rng.integers(n_ext)))), N, seg, m=N))
+    ext = [TensorSpec("bf16", N) for _ in range(n_ext)]
+    ints = [TensorSpec("bf16", N * (2 if i == big else 1)) for i in range(n_int)]
+    return ChainSpec(f"decoder_like_{seed}_{rows}x{H}", ks, ext, ints, weights, sorted(written), 7700 + seed,
+                     meta={"out_numel": N})
+
+
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_decoder_like_chain(seed):
+    """Bit-identity of every replay mode with eager launches, and every kernel against the oracle, on chains that
+    the planner turns into GEMV dispatches with prologues, epilogues and renamed buffers."""
+    spec = random_decoder_like_chain(seed)
+    N = spec.meta["out_numel"]
+    rng = np.random.Generator(np.random.PCG64(seed))
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels {[k.op for k in spec.kernels]} in {merged} dispatches, segments {spec.kernels[-1].segment + 1}")
+    h.chain.capture(h.stream)
+    n_seg = spec.kernels[-1].segment + 1
+    has_ext = [any(r.kind == EXT for k in spec.kernels if k.segment == s for r in k.ins) for s in range(n_seg)]
+    for t in range(2):
+        x_np = make_inputs(spec, t)
+        placed = [place(x, int(rng.choice([0, 0, 2, 4, 8]))) for x in x_np]
+        ptrs = [p for _, p in placed]
+        ref = [o[:N] for o in h.run("eager", ptrs)]
+        for mode in ("copy", "indirect"):
+            h.scrub()
+            got = h.run(mode, ptrs)
+            for a, b in zip(got, ref):
+                assert same_bits(a[:N], b), (mode, t)
+        h.scrub()
+        h.chain.replay_update(ptrs, h.stream)
+        h.stream.synchronize()
+        for o, b in zip(spec.outputs, ref):
+            assert same_bits(h.chain.output(o)[:N], b), ("update", t)
+        for _ in range(2):
+            modes = [int(rng.choice([0, 1, 2] if has_ext[s] else [0, 1])) for s in range(n_seg)]
+            h.scrub()
+            got = h.run("selected", ptrs, modes=modes)
+            for a, b in zip(got, ref):
+                assert same_bits(a[:N], b), ("selected", modes, t)
+        if t == 0:
+            h.scrub()
+            stepwise_check(h, x_np, ptrs)
+    h.close()
