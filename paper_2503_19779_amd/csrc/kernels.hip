@@ -1108,22 +1108,26 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
 // RMSNorm of the rows the narrow form has just loaded, as a prologue (FULL, 2048 columns): lane (wave, l)
 // holds 16-byte chunk c of every row, where c runs over all 256 chunks of a row across the workgroup, but
 // not in lane order.  The stand-alone kernel's sums must be reproduced bit for bit: per chunk the fused
-// sum of squares in element order (any lane can do that), then the chunk sums travel through LDS to the
-// lane the stand-alone kernel would have had them in (lane t <-> chunk t), where wave_sum and the fixed
-// order of the four wave sums follow; lane r < NRH turns row r's total into its scale, and every lane
-// scales its own chunks: (x * scale) * gain, one rounding.  `scratch`: NRH * 256 + NRH * 4 + NRH floats of
-// LDS that nothing else uses until the rows are staged.  hstore: this workgroup also stores the rows.
+// sum of squares in element order (any lane can do that); then the stand-alone kernel's reduction, which
+// is a tree of fixed shape over the chunk sums in chunk order -- wave_sum adds neighbours, then pairs of
+// pairs, of quads, of eights (a floating-point add does not care which operand is which), then the four
+// sixteens in order, and the four wave sums in order.  Here the chunk sums go to LDS in chunk order and
+// the workgroup's 16 * NRH subtrees of sixteen leaves are spread over its lanes, one each; lane r < NRH
+// then finishes row r (four sixteens per wave sum, four wave sums) and turns the total into the row's
+// scale; every lane scales its own chunks: (x * scale) * gain, one rounding.  `scratch`: NRH * 336 + NRH
+// floats of LDS that nothing else uses until the rows are staged.  hstore: this workgroup also stores the rows.
 template <int NRH>
 __device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned* wg /* the lane's chunk of the gain */, float eps, bf16_t* hstore,
                                                 int rows, int wave, int lane, float* scratch) {
     constexpr int kCols = 32 * 4 * kMmSteps;
+    constexpr int kRow = 256 + 64;             // a row of chunk sums, 8 floats of padding after every 32: the lanes of a wave hold
+                                               // chunks 32 apart, which would otherwise all fall into the same eight banks
     const int tid = wave * 64 + lane;
     const int k0 = mm_k0(0, wave, lane);
-    float* sq = scratch;                       // [NRH][256]: chunk sums, indexed by chunk (bits 3-4 swizzled with bits 5-6: the lanes of
-                                               // a wave hold chunks 32 apart, which would all fall into the same eight banks)
-    float* part = scratch + NRH * 256;         // [NRH][4]: wave sums
-    float* scale = part + NRH * 4;             // [NRH]
-    auto at = [](int c) { return c ^ (((c >> 5) & 3) << 3); };
+    float* sq = scratch;                       // [NRH][kRow]: chunk sums in chunk order
+    float* six = scratch + NRH * kRow;         // [NRH][16]: sums of sixteen chunks
+    float* scale = six + NRH * 16;             // [NRH]
+    auto at = [](int c) { return c + 8 * (c >> 5); };
     float fx[NRH][8];
 #pragma unroll
     for (int r = 0; r < NRH; r++) {
@@ -1131,18 +1135,23 @@ __device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned
         float acc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e++) acc = __builtin_fmaf(fx[r][e], fx[r][e], acc);
-        sq[r * 256 + at(k0 >> 3)] = acc;
+        sq[r * kRow + at(k0 >> 3)] = acc;
     }
     lds_barrier();
-#pragma unroll
-    for (int r = 0; r < NRH; r++) {
-        const float acc = wave_sum(sq[r * 256 + at(tid)]);
-        if (lane == 0) part[r * 4 + wave] = acc;
+    if (tid < 16 * NRH) {                      // subtree tid: row tid / 16, chunks 16 * (tid % 16) .. + 15
+        const f32x4* leaf = reinterpret_cast<const f32x4*>(sq + (tid >> 4) * kRow + at((tid & 15) * 16));
+        const f32x4 l0 = leaf[0], l1 = leaf[1], l2 = leaf[2], l3 = leaf[3];
+        const float q0 = (l0.x + l0.y) + (l0.z + l0.w), q1 = (l1.x + l1.y) + (l1.z + l1.w);
+        const float q2 = (l2.x + l2.y) + (l2.z + l2.w), q3 = (l3.x + l3.y) + (l3.z + l3.w);
+        six[tid] = (q0 + q1) + (q2 + q3);
     }
     lds_barrier();
     if (tid < NRH) {
-        const float* prow = part + tid * 4;
-        const float total = ((prow[0] + prow[1]) + prow[2]) + prow[3];
+        const f32x4* sx = reinterpret_cast<const f32x4*>(six + tid * 16);
+        float wsum[4];
+#pragma unroll
+        for (int w = 0; w < 4; w++) wsum[w] = ((sx[w].x + sx[w].y) + sx[w].z) + sx[w].w;
+        const float total = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
         scale[tid] = 1.0f / sqrtf(total / (float)kCols + eps);
     }
     lds_barrier();
@@ -1179,7 +1188,7 @@ __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf1
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if constexpr (PRO) {
         static_assert(FULL, "the prologue exists for rows of 2048 columns");
-        static_assert((NRH * 256 + NRH * 5) * sizeof(float) <= 4 * kMmWaveLds, "the prologue's sums fit the staging area");
+        static_assert((NRH * 336 + NRH) * sizeof(float) <= 4 * kMmWaveLds, "the prologue's sums fit the staging area");
         mm_rmsnorm_rows<NRH>(g, wg, eps, hstore, rows, wave, lane, reinterpret_cast<float*>(stage));
         lds_barrier();        // the sums are read: the staging area takes the rows now
     }
