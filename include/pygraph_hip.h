@@ -267,7 +267,7 @@ pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */
  * kernel of the run wrote in any other pattern than element for element.  Likewise up to 3 elementwise
  * kernels over the outputs of a bf16 GEMV over rows of 2048 columns (GELU of the result, the residual
  * add, an input add) ride in the GEMV's dispatch as an epilogue: each lane that holds a finished output
- * rounds it as the GEMV's store would and runs the following kernels on that element.  Up to 16 rows of
+ * rounds it as the GEMV's store would and runs the following kernels on that element.  Up to 32 rows of
  * h the RMSNorm that produces the GEMV's input rides in front of it as a prologue (every workgroup
  * normalises the rows itself, one stores them); a run whose epilogue overwrites the buffer its prologue
  * reads writes a second copy of that buffer, which the workspace holds (pg_chain_workspace_bytes counts

@@ -168,7 +168,9 @@ const void* merged_kernel(int dtype, bool narrow);
 bool merge_head(int op, int dtype, const Shape& shape, long long* n_out);
 // The epilogue form for that many rows of h; launched with the grid and row groups plan() gives the plain
 // GEMV of the same shape.  A prologue exists up to kPrologueMaxRows rows (null otherwise).
-constexpr int kPrologueMaxRows = 16;
+// Up to two tiles of 16 rows, one per workgroup, fill the 256 CUs once; beyond, two workgroups share a CU and each
+// normalises its tile, which costs more than the dispatch it saves (decode chain at 48 rows: 1261 -> 1336 us).
+constexpr int kPrologueMaxRows = 32;
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue);
 
 }  // namespace pgk

@@ -1029,9 +1029,16 @@ __device__ __forceinline__ void mm_reduce_store(float* red, f32x4 acc, Emit& emi
     emit.end();
 }
 
-template <bool FULL, bool SINGLE, bool AL, class Emit>
+// mm_rmsnorm_rows is defined with the narrow form below
+template <int NRH>
+__device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned* wg, float eps, bf16_t* hstore, int rows, int wave, int lane, float* scratch);
+
+// PRO (SINGLE, FULL, one tile of rows per workgroup -- rows < kMmWideRows): h points at the rows to normalise,
+// the workgroups of column block 0 store the normalised rows to hstore (see mm_rmsnorm_rows).
+template <bool FULL, bool SINGLE, bool AL, bool PRO = false, class Emit>
 __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols, int row_groups,
-                                               char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */) {
+                                               char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */,
+                                               const bf16_t* gain = nullptr, float eps = 0.f, bf16_t* hstore = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
     const int ncb = (n + 15) / 16;
@@ -1050,8 +1057,16 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
         // for all tiles of the workgroup, and a later tile's rows are in flight across the multiplies
         // of the one before.
         mm_load_rows<FULL, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
+        unsigned wg[4] = {0u, 0u, 0u, 0u};
+        if constexpr (PRO) load_vec_global<bf16_t, AL, false>(gain + mm_k0(0, wave, lane), wg);   // before the weights: loads come back in order
         mm_load_rows<FULL, AL>(W, n, cols, j0, 0, wave, lane, gw);
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (PRO) {
+            static_assert(FULL && SINGLE, "the prologue exists for rows of 2048 columns");
+            bf16_t* tile_store = (hstore && cb == 0) ? hstore + (size_t)t0 * 16 * (32 * 4 * kMmSteps) : nullptr;
+            mm_rmsnorm_rows<16>(g, wg, eps, tile_store, rows - t0 * 16, wave, lane, reinterpret_cast<float*>(stage));
+            lds_barrier();        // the sums are read: the staging area takes the rows now
+        }
         mm_stage(lds, lane, g);
         mm_read_frags(lds, lane, a);
         mm_zero_tail<FULL>(a, cols, 0, wave, kq);
@@ -1332,12 +1347,13 @@ __device__ __forceinline__ void mm_epilogue_setup(const GemvEpiArgs& p, MmEpilog
 }
 template <int FORM, bool PRO = false>
 __global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfma_epilogue(GemvEpiArgs p) {
-    static_assert(!PRO || FORM <= 1, "a prologue exists for the narrow forms only");
+    static_assert(!PRO || FORM <= 2, "a prologue exists for the forms with one tile of rows per workgroup");
     const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, p.head & 1u));
     // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where workgroup 0 stores it
     const bf16_t* h = static_cast<const bf16_t*>(PRO ? resolve_rt(p.x, p.head & kEpiXSlot) : resolve_rt(p.g.h, p.head & 2u));
     const bf16_t* gain = PRO ? static_cast<const bf16_t*>(resolve_rt(p.gain, p.head & kEpiGainSlot)) : nullptr;
-    bf16_t* hstore = (PRO && (p.head & kEpiStoreH) && blockIdx.x == 0) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
+    // the narrow forms have one workgroup per column block: the first stores; the 16-column form picks its column block 0 itself
+    bf16_t* hstore = (PRO && (p.head & kEpiStoreH) && (FORM == 2 || blockIdx.x == 0)) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[(FORM == 3 ? 2 : 1) * 4 * 64 * 4];
     MmEpilogue<FORM == 3 ? 2 : 1> emit;
@@ -1350,8 +1366,8 @@ __global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfm
         if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
         else gemm_mfma_narrow_body<true, false, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
     } else if constexpr (FORM == 2) {
-        if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
-        else gemm_mfma_body<true, true, false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+        if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red, gain, p.eps, hstore);
+        else gemm_mfma_body<true, true, false, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red, gain, p.eps, hstore);
     } else {
         if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
         else gemm_mfma_wide_body<false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
@@ -2067,11 +2083,13 @@ bool merge_head(int op, int dtype, const Shape& s, long long* n_out) {
     return true;
 }
 
+static_assert(kPrologueMaxRows < kMmWideRows, "a prologue exists only where a workgroup owns one tile of rows");
 const void* gemv_epilogue_kernel(int rows_of_h, bool with_prologue) {
     if (rows_of_h > 4) {
         if (with_prologue) {
             if (rows_of_h <= 8) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<0, true>);
             if (rows_of_h <= 16) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<1, true>);
+            if (rows_of_h <= kPrologueMaxRows) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<2, true>);
             return nullptr;
         }
         if (rows_of_h <= 8) return reinterpret_cast<const void*>(&k_gemm_mfma_epilogue<0>);
