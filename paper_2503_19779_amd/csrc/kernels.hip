@@ -274,7 +274,46 @@ __device__ __forceinline__ void lds_barrier() {
 // tail).  For fp32 tensors it is evaluated in fp64 and rounded once, so that the result is the
 // correctly rounded one except within ~1e-16 of a rounding boundary: an fp32 erfc is a few ulp off,
 // and a chain of multiplies and cancelling adds amplifies that beyond 1e-5.  For bf16 tensors fp32
-// is far more than the 8 stored bits need.
+// is far more than the 8 stored bits need, and the library erfcf (a few hundred instructions over
+// several branches, which a wave of mixed values all takes) made large GELU kernels ALU-bound at a
+// quarter of the HBM rate; gelu_bf16 below is branch-free and about 40 instructions.
+//
+// erfc(z), z >= 0, as (1 - u) * exp(-z^2 + u * Q(u)) with u = z / (2 + z) in [0, 1): the exponent's
+// second term is log(erfc(z) exp(z^2) (1 + z/2)), smooth in u and zero at u = 0, so that erfc(0) = 1
+// comes out exactly and tiny inputs give a/2 exactly.  Q: degree 9, a Chebyshev fit on z <= 9.7
+// (beyond, a * Phi(a) is below the smallest normal number), max error 8e-9 in the exponent.  z^2 is
+// taken with its rounding error (one fma), the exponential as 2^k * exp2(r) with |r| <= 0.51 after a
+// two-constant reduction, so the relative error stays near 2e-7 into the tail.  Checked against the
+// fp64 definition on every finite bf16 input: the bf16 result is the correctly rounded one for all
+// of them (the closest any exact value comes to a rounding boundary is 8e-7, at a = -0.336).
+__device__ __forceinline__ float gelu_bf16(float a) {
+    const float x = a * -0.70710678118654752440f;
+    const float z = __builtin_fminf(__builtin_fabsf(x), 14.0f);      // erfc(14) = 0 in fp32; keeps z * z finite (and a NaN out of the exponent)
+    const float u = z * __builtin_amdgcn_rcpf(2.0f + z);
+    const float t = 1.0f - u;
+    float p = -0.153892517f;
+    p = __builtin_fmaf(p, u, 0.49560681f);
+    p = __builtin_fmaf(p, u, -0.509543419f);
+    p = __builtin_fmaf(p, u, 0.182105958f);
+    p = __builtin_fmaf(p, u, -0.144903973f);
+    p = __builtin_fmaf(p, u, 0.072065711f);
+    p = __builtin_fmaf(p, u, 0.19142893f);
+    p = __builtin_fmaf(p, u, 0.161542267f);
+    p = __builtin_fmaf(p, u, -0.303239733f);
+    p = __builtin_fmaf(p, u, -1.25675833f);
+    p = p * u;
+    const float s = z * z, e = __builtin_fmaf(z, z, -s);               // z^2 = s + e exactly
+    constexpr float kLog2e = 1.4426950408889634f, kLn2Hi = 0.693145751953125f, kLn2Lo = 1.42860682030941723212e-6f;
+    const float kf = __builtin_rintf((p - s) * kLog2e);
+    float r = __builtin_fmaf(kf, -kLn2Hi, -s);
+    r = r + p;
+    r = r - e;
+    r = __builtin_fmaf(kf, -kLn2Lo, r);
+    const float v = __builtin_ldexpf(t * __builtin_amdgcn_exp2f(r * kLog2e), (int)kf);
+    const float erfc_x = x < 0.f ? 2.0f - v : v;
+    return (0.5f * a) * erfc_x;      // a NaN comes back through this product; -inf * 0 = NaN as in the definition
+}
+
 template <int OP, bool WIDE>
 __device__ __forceinline__ float ew_apply(float a, float b) {
     if constexpr (OP == kAdd) {
@@ -285,7 +324,7 @@ __device__ __forceinline__ float ew_apply(float a, float b) {
         const double x = (double)a;
         return (float)((0.5 * x) * erfc(x * -0.70710678118654752440));
     } else {
-        return (0.5f * a) * erfcf(a * -0.70710678118654752440f);
+        return gelu_bf16(a);
     }
 }
 

@@ -103,6 +103,27 @@ def test_gelu_special_values(dtype):
     assert np.all(np.abs(got - want) <= rel * np.abs(want) + 1e-37)   # pure relative, the left tail included
 
 
+def test_gelu_bf16_every_input():
+    """All 65536 bf16 bit patterns through the GELU kernel (the 16-byte form) and, as a tensor of 16384
+    elements less, through whichever form a small tensor takes: for every finite input the stored bf16 is
+    the one the fp64 definition rounds to (the kernel's fp32 evaluation stays inside the distance that
+    separates each exact value from its nearest rounding boundary); a NaN stays a NaN."""
+    a = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    for lo, hi in ((0, 65536), (0, 4096), (4096, 4096 + 1000)):
+        part = a[lo:hi].copy()
+        n = part.size
+        say(f"gelu bf16 bit patterns {lo:#x}..{hi:#x}")
+        spec = ChainSpec("g", [KernelSpec("gelu", "bf16", 0, (Ref(EXT, 0),), n)], [TensorSpec("bf16", n)], [TensorSpec("bf16", n)], [], [0])
+        got = run_single(spec, [part], [])
+        want = oracle.run_chain(spec, [], [part])[0]
+        nan_in = (part & 0x7fff) > 0x7f80
+        nan_want = (want & 0x7fff) > 0x7f80          # NaN inputs and -inf (-inf * 0)
+        assert np.all(nan_want[nan_in])
+        assert np.array_equal((got & 0x7fff) > 0x7f80, nan_want)
+        differ = np.nonzero((got != want) & ~nan_want)[0]
+        assert differ.size == 0, [(hex(part[i]), hex(got[i]), hex(want[i])) for i in differ[:10]]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("rows,cols,off", [(1, 8, 0), (3, 100, 0), (1, 2048, 0), (5, 2048, 0), (2, 8200, 0), (2, 9000, 0),
                                             (1, 2048, 4), (3, 37, 0)])
