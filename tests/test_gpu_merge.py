@@ -151,6 +151,45 @@ def test_prologue_hazards(rows):
     h.close()
 
 
+@pytest.mark.parametrize("rows,n", [(1, 1027), (3, 1100), (4, 2040), (6, 1030), (8, 40), (12, 72), (16, 1029), (17, 33), (20, 1030), (32, 48),
+                                    (32, 1100), (33, 1030)])
+def test_prologue_with_other_output_widths(rows, n):
+    """RMSNorm -> GEMV -> GELU -> add where the GEMV's output has n columns, not the 2048 of the stream (a ragged
+    last column block in every form, fewer column blocks than CUs, a single one): the prologue rides in front
+    (up to 32 rows), the normalised rows are stored once, and a later kernel reads them back."""
+    H = 2048
+    N = rows * n
+    ks = [KernelSpec("add", "bf16", 0, (Ref(EXT, 0), Ref(EXT, 0)), rows * H, m=rows * H),                       # x = 2 e0
+          KernelSpec("rmsnorm", "bf16", 1, (Ref(INT, 0), Ref(WEIGHT, 1)), H, rows=rows, cols=H, eps=1e-6),      # t = norm(x)
+          KernelSpec("gemv", "bf16", 2, (Ref(WEIGHT, 0), Ref(INT, 1)), n, rows=rows, cols=H),                   # y = t W^T
+          KernelSpec("gelu", "bf16", 2, (Ref(INT, 2),), N),
+          KernelSpec("add", "bf16", 2, (Ref(INT, 2), Ref(EXT, 1)), N, m=N),
+          KernelSpec("mul", "bf16", 0, (Ref(INT, 0), Ref(INT, 1)), rows * H, m=rows * H),                       # x = x * t: reads the stored rows
+          KernelSpec("rmsnorm", "bf16", 1, (Ref(EXT, 0), Ref(WEIGHT, 1)), H, rows=rows, cols=H, eps=1e-6),      # external x this time
+          KernelSpec("gemv", "bf16", 3, (Ref(WEIGHT, 0), Ref(INT, 1)), n, rows=rows, cols=H),
+          KernelSpec("add", "bf16", 3, (Ref(INT, 3), Ref(INT, 2)), N, m=N),
+          ]
+    spec = ChainSpec(f"prologue_width_{rows}x{n}", ks,
+                     [TensorSpec("bf16", rows * H), TensorSpec("bf16", N)],
+                     [TensorSpec("bf16", rows * H), TensorSpec("bf16", rows * H), TensorSpec("bf16", N), TensorSpec("bf16", N)],
+                     [TensorSpec("bf16", n * H, ("normal", 0.0, 0.02)), TensorSpec("bf16", H, ("normal", 1.0, 0.1))],
+                     [0, 1, 2, 3], 6020)
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
+    # up to 32 rows [add] [RMSNorm, GEMV, GELU, add] [mul] [RMSNorm, GEMV, add]; above, each RMSNorm joins the elementwise kernel in front of it
+    assert merged == 4, (merged, unmerged)
+    h.chain.capture(h.stream)
+    for t in range(3):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        for o in range(len(spec.outputs)):
+            assert same_bits(outs["eager"][o], outs["copy"][o]) and same_bits(outs["eager"][o], outs["indirect"][o]), (t, o)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
+    h.close()
+
+
 @pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100),
                                     (5, 1027), (8, 2048), (13, 1030), (16, 40), (17, 1100), (40, 1029), (63, 48), (64, 1030), (100, 2048), (130, 70)])
 def test_gemv_with_elementwise_epilogue(rows, n):
