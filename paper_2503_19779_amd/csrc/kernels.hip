@@ -26,11 +26,16 @@ namespace {
 
 constexpr int kBlock = 256;   // threads per workgroup = 4 waves of 64
 
+#define PG_GLOBAL __attribute__((address_space(1)))
+#define PG_CONSTANT __attribute__((address_space(4)))
+
 // ---- operand resolution -------------------------------------------------------------------
 template <bool IND>
 __device__ __forceinline__ const void* resolve(const void* p) {
     if constexpr (IND) {
-        return *reinterpret_cast<const void* const*>(p);   // uniform address: one scalar load
+        // uniform address: one scalar load.  What a slot holds is a tensor in global memory; saying so lets the
+        // compiler use global loads where it would otherwise fall back to generic ones (which also count as LDS operations)
+        return (const void*)(const void PG_GLOBAL*)*reinterpret_cast<const uintptr_t*>(p);
     } else {
         return p;
     }
@@ -125,8 +130,6 @@ __device__ __forceinline__ void load_vec(const T* p, unsigned* w) {
 // The same fetch through a pointer that says "global memory" outright.  A tensor address that reached the
 // kernel through a pointer-table slot or a run-time choice is a generic pointer to the compiler; generic
 // loads are slower and are counted as LDS operations as well, so a wait for LDS would wait for them too.
-#define PG_GLOBAL __attribute__((address_space(1)))
-#define PG_CONSTANT __attribute__((address_space(4)))
 template <typename T, bool AL, bool NT = false>
 __device__ __forceinline__ void load_vec_global(const T* p, unsigned* w) {
     if constexpr (AL) {
@@ -892,7 +895,7 @@ __device__ __forceinline__ void mm_load_rows(const bf16_t* h, int rows, int cols
 #pragma unroll
     for (int r = 0; r < NR; r++) {
         const int R = r0 + r < rows ? r0 + r : rows - 1;
-        load_vec<bf16_t, 16, AL, false>(h + (size_t)R * cols + koff, g[r]);
+        load_vec_global<bf16_t, AL, false>(h + (size_t)R * cols + koff, g[r]);     // global outright: see load_vec_global
     }
 }
 
@@ -935,35 +938,119 @@ __device__ __forceinline__ void mm_mfma(const v4u* a, const v4u* b, f32x4& acc) 
 // MmStore: the stand-alone kernels -- each sum is rounded and stored.
 template <int NE>
 struct MmStore {
+    static constexpr bool kEarly = false;
     bf16_t* y;
     int rows, n;
     size_t at = 0;
     int r = 0;
     bool col_ok = false;
+    __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void begin(int r_, int j, bool ok) { r = r_; col_ok = ok; at = (size_t)r_ * n + j; }
     __device__ __forceinline__ void put(int k, float v) { if (col_ok && r + k < rows) store_elem(y + at + (size_t)k * n, v); }
     __device__ __forceinline__ void end() {}
 };
 // MmEpilogue: the kernels that follow the GEMV in the chain, element for element, ride along (kernels.h,
-// GemvEpiArgs): begin() asks for their operands, so that they arrive while the tile is multiplied and the
-// partial sums are exchanged; end() plays the kernels on the lane's outputs, rounding to bf16 after each as
-// the stand-alone kernels do, with the GELU as the only branch.
-template <int NE>
+// GemvEpiArgs): prepare() reads their table out of the kernel arguments and resolves pointer-table slots --
+// the bodies call it once their weight loads are on their way, as k_gemv_epilogue does, so that nothing but
+// the first 64 bytes of the arguments stands between the start of the kernel and those loads; begin() asks
+// for the operands, so that they arrive while the tile is staged and multiplied and the partial sums are
+// exchanged; end() plays the kernels on the lane's outputs, rounding to bf16 after each as the stand-alone
+// kernels do, with the GELU as the only branch.
+// EARLY (the narrow forms, whose few loads leave the operands' latency exposed): begin() comes right behind the
+// weight loads and always issues the same number of loads -- an operand that comes from a register slot is
+// fetched from the GEMV's own output buffer instead and ignored -- so that every wait on the rows and weights
+// knows exactly how many younger loads are outstanding.  Otherwise the loads are conditional, which the compiler
+// cannot count (a wait for an older load placed behind them would wait for more than it needs), and begin() comes
+// once the rows and weights of the tile have been taken out of their registers, in front of the multiplies.
+template <int NE, bool EARLY>
 struct MmEpilogue {
+    static constexpr bool kEarly = EARLY;
     static constexpr int P = kEpiMaxPhases;
     bf16_t* y;
     int rows, n;
     unsigned head;
     int n_epi;
+    const void PG_CONSTANT* ka;   // the kernel-argument segment (a GemvEpiArgs)
+    float eps = 0.f;              // the prologue's, read with the table
     const bf16_t* q0[P];        // operand addresses, pointer-table slots resolved; null: comes from a register slot
     const bf16_t* q1[P];
     bf16_t* outs[P];
     unsigned ms[P], metas[P], inds[P];
+    bool plain = true;          // EARLY: no operand has a broadcast period
     // per call
     unsigned idx[NE];
     bool ok[NE];
     unsigned ld0[P][NE], ld1[P][NE];
     float v[NE];
+    __device__ __forceinline__ void prepare() {
+        static_assert(P == 3, "the argument batch names every phase");
+        using SlotPtr = const void* const PG_CONSTANT*;
+        const void* a0[P];
+        const void* a1[P];
+        {   // through the segment's address made opaque: otherwise the compiler moves these loads (invariant
+            // memory) to the top of the kernel, in front of the weight loads
+            const GemvEpiArgs PG_CONSTANT* kp = (const GemvEpiArgs PG_CONSTANT*)ka;
+            asm volatile("" : "+s"(kp));
+            eps = kp->eps;
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                a0[i] = kp->ph[i].in0; a1[i] = kp->ph[i].in1; outs[i] = static_cast<bf16_t*>(kp->ph[i].out);
+                ms[i] = kp->ph[i].m; metas[i] = kp->ph[i].meta; inds[i] = kp->ph[i].ind;
+            }
+            asm volatile("" : "+s"(eps),
+                              "+s"(a0[0]), "+s"(a1[0]), "+s"(outs[0]), "+s"(ms[0]), "+s"(metas[0]), "+s"(inds[0]),
+                              "+s"(a0[1]), "+s"(a1[1]), "+s"(outs[1]), "+s"(ms[1]), "+s"(metas[1]), "+s"(inds[1]),
+                              "+s"(a0[2]), "+s"(a1[2]), "+s"(outs[2]), "+s"(ms[2]), "+s"(metas[2]), "+s"(inds[2]));
+        }
+        bool f0[P], f1[P], s0[P], s1[P];
+        unsigned any = 0;
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            const unsigned mt = metas[i];
+            f0[i] = ((mt >> 8) & 0xffu) == kMergeFromMemory;
+            f1[i] = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
+            s0[i] = f0[i] && (inds[i] & 1u);
+            s1[i] = f1[i] && (inds[i] & 2u);
+            any |= (f0[i] ? inds[i] & 1u : 0u) | (f1[i] ? inds[i] & 2u : 0u);
+        }
+        any = __builtin_amdgcn_readfirstlane(any);
+        asm volatile("" : "+s"(any));       // keeps what follows behind the weight loads
+        if (any) {                           // some operand is a pointer-table slot: all in one batch, without branches
+            auto slot_addr = [&](const void* q, bool is_slot) -> SlotPtr { return is_slot ? (SlotPtr)(uintptr_t)q : (SlotPtr)ka; };
+            SlotPtr at0[P], at1[P];
+            const void* t0[P];
+            const void* t1[P];
+#pragma unroll
+            for (int i = 0; i < P; i++) { at0[i] = slot_addr(a0[i], s0[i]); at1[i] = slot_addr(a1[i], s1[i]); }
+#pragma unroll
+            for (int i = 0; i < P; i++) { t0[i] = *at0[i]; t1[i] = *at1[i]; }
+            asm volatile("" : "+s"(t0[0]), "+s"(t1[0]), "+s"(t0[1]), "+s"(t1[1]), "+s"(t0[2]), "+s"(t1[2]));
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                if (s0[i]) a0[i] = t0[i];
+                if (s1[i]) a1[i] = t1[i];
+            }
+        }
+        if constexpr (EARLY) {
+            const unsigned total = (unsigned)rows * (unsigned)n;
+            plain = true;
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                q0[i] = f0[i] ? static_cast<const bf16_t*>(a0[i]) : y;
+                q1[i] = f1[i] ? static_cast<const bf16_t*>(a1[i]) : y;
+                ms[i] = f1[i] ? ms[i] : total;
+                plain = plain && ms[i] == total;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                q0[i] = f0[i] ? static_cast<const bf16_t*>(a0[i]) : nullptr;
+                q1[i] = f1[i] ? static_cast<const bf16_t*>(a1[i]) : nullptr;
+#pragma unroll
+                for (int k = 0; k < NE; k++) ld0[i][k] = ld1[i][k] = 0u;
+            }
+        }
+    }
     __device__ __forceinline__ void begin(int r, int j, bool col_ok) {
         const unsigned total = (unsigned)rows * (unsigned)n;
 #pragma unroll
@@ -971,16 +1058,36 @@ struct MmEpilogue {
             ok[e] = col_ok && r + e < rows;
             idx[e] = ok[e] ? (unsigned)(r + e) * (unsigned)n + (unsigned)j : 0u;
         }
+        if constexpr (EARLY) {
+            if (__builtin_expect(plain, 1)) {      // the usual case, one branch for all
 #pragma unroll
-        for (int i = 0; i < P; i++) {
-            if (i < n_epi && q0[i]) {
+                for (int i = 0; i < P; i++)
 #pragma unroll
-                for (int e = 0; e < NE; e++) ld0[i][e] = load_raw_global_at(q0[i], idx[e]);
+                    for (int e = 0; e < NE; e++) {
+                        ld0[i][e] = load_raw_global_at(q0[i], idx[e]);
+                        ld1[i][e] = load_raw_global_at(q1[i], idx[e]);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < P; i++)
+#pragma unroll
+                    for (int e = 0; e < NE; e++) {
+                        ld0[i][e] = load_raw_global_at(q0[i], idx[e]);
+                        ld1[i][e] = load_raw_global_at(q1[i], idx[e] % ms[i]);
+                    }
             }
-            if (i < n_epi && q1[i]) {
-                const unsigned m = ms[i];
+        } else {
 #pragma unroll
-                for (int e = 0; e < NE; e++) ld1[i][e] = load_raw_global_at(q1[i], m == total ? idx[e] : idx[e] % m);
+            for (int i = 0; i < P; i++) {
+                if (i < n_epi && q0[i]) {
+#pragma unroll
+                    for (int e = 0; e < NE; e++) ld0[i][e] = load_raw_global_at(q0[i], idx[e]);
+                }
+                if (i < n_epi && q1[i]) {
+                    const unsigned m = ms[i];
+#pragma unroll
+                    for (int e = 0; e < NE; e++) ld1[i][e] = load_raw_global_at(q1[i], m == total ? idx[e] : idx[e] % m);
+                }
             }
         }
     }
@@ -1077,7 +1184,7 @@ __device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned
 template <bool FULL, bool SINGLE, bool AL, bool PRO = false, class Emit>
 __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols, int row_groups,
                                                char* stage /* LDS: 4 x kMmWaveLds */, float* red /* LDS: [4 waves][64 lanes][4] */,
-                                               const bf16_t* gain = nullptr, float eps = 0.f, bf16_t* hstore = nullptr) {
+                                               const bf16_t* gain = nullptr, const float& eps = 0.f /* read by emit.prepare() */, bf16_t* hstore = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
     const int ncb = (n + 15) / 16;
@@ -1099,6 +1206,7 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
         unsigned wg[4] = {0u, 0u, 0u, 0u};
         if constexpr (PRO) load_vec_global<bf16_t, AL, false>(gain + mm_k0(0, wave, lane), wg);   // before the weights: loads come back in order
         mm_load_rows<FULL, AL>(W, n, cols, j0, 0, wave, lane, gw);
+        emit.prepare();                                      // the epilogue's table right behind the weight loads
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (PRO) {
             static_assert(FULL && SINGLE, "the prologue exists for rows of 2048 columns");
@@ -1130,6 +1238,7 @@ __device__ __forceinline__ void gemm_mfma_body(const bf16_t* W, const bf16_t* h,
             mm_reduce_store(red, acc, emit, wave, lane);
         }
     } else {
+        emit.prepare();
 #pragma unroll 1
         for (int t = t0; t < t1; t++) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -1228,7 +1337,8 @@ __device__ __forceinline__ void mm_rmsnorm_rows(unsigned (*g)[4], const unsigned
 
 template <bool FULL, bool AL, int NRH, bool PRO = false, class Emit>
 __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols,
-                                                      char* stage, float* red, const bf16_t* gain = nullptr, float eps = 0.f, bf16_t* hstore = nullptr) {
+                                                      char* stage, float* red, const bf16_t* gain = nullptr, const float& eps = 0.f /* read by emit.prepare() */,
+                                                      bf16_t* hstore = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kq = lane >> 4;
     const int j0 = blockIdx.x * 8, r0 = 0;
@@ -1239,6 +1349,8 @@ __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf1
     unsigned wg[4] = {0u, 0u, 0u, 0u};
     if constexpr (PRO) load_vec_global<bf16_t, AL, false>(gain + mm_k0(0, wave, lane), wg);   // before the weights: loads come back in order
     mm_load_rows<FULL, AL, 8>(W, n, cols, j0, 0, wave, lane, gw);
+    emit.prepare();                                          // the epilogue's table right behind the weight loads
+    if constexpr (Emit::kEarly) mm_emit_begin<8>(emit, n, r0, j0, wave, lane);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if constexpr (PRO) {
         static_assert(FULL, "the prologue exists for rows of 2048 columns");
@@ -1253,7 +1365,7 @@ __device__ __forceinline__ void gemm_mfma_narrow_body(const bf16_t* W, const bf1
     mm_read_frags(lds, lane, b);
     mm_zero_tail<FULL>(b, cols, 0, wave, kq);
     __builtin_amdgcn_sched_barrier(0);
-    mm_emit_begin<8>(emit, n, r0, j0, wave, lane);
+    if constexpr (!Emit::kEarly) mm_emit_begin<8>(emit, n, r0, j0, wave, lane);
     mm_mfma(a, b, acc);
     mm_reduce_store(red, acc, emit, wave, lane);
 }
@@ -1291,6 +1403,7 @@ __device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_
     mm_load_rows<true, AL>(h, rows, cols, t0 * 16, 0, wave, lane, g);
     mm_load_rows<true, AL>(W, n, cols, j0, 0, wave, lane, gw0);
     mm_load_rows<true, AL>(W, n, cols, j0 + 16, 0, wave, lane, gw1);
+    emit.prepare();      // the epilogue's table right behind the weight loads
     mm_stage(lds, lane, g);
     mm_read_frags(lds, lane, a);
     if (t1 - t0 > 1) mm_load_rows<true, AL>(h, rows, cols, (t0 + 1) * 16, 0, wave, lane, g);
@@ -1362,54 +1475,59 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16(GemvArgs p) {
 // The matrix-core forms with an elementwise epilogue (kernels.h, GemvEpiArgs; no prologue): the same bodies,
 // with MmEpilogue in place of the plain store.  Only for rows of 2048 columns.  FORM 0: narrow, 8 rows of h
 // loaded; 1: narrow, 16; 2: 16 columns per workgroup, one pass over K; 3: wide.
-template <int NE>
-__device__ __forceinline__ void mm_epilogue_setup(const GemvEpiArgs& p, MmEpilogue<NE>& e) {
-    e.y = static_cast<bf16_t*>(p.g.out);
-    e.rows = p.g.rows;
-    e.n = p.g.n;
-    e.head = p.head;
-    e.n_epi = p.n_epi;
-#pragma unroll
-    for (int i = 0; i < MmEpilogue<NE>::P; i++) {
-        const unsigned mt = p.ph[i].meta, ind = p.ph[i].ind;
-        const bool f0 = ((mt >> 8) & 0xffu) == kMergeFromMemory;
-        const bool f1 = (mt & 0xffu) != kGelu && ((mt >> 16) & 0xffu) == kMergeFromMemory;
-        e.q0[i] = f0 ? static_cast<const bf16_t*>(resolve_rt(p.ph[i].in0, ind & 1u)) : nullptr;
-        e.q1[i] = f1 ? static_cast<const bf16_t*>(resolve_rt(p.ph[i].in1, ind & 2u)) : nullptr;
-        e.outs[i] = static_cast<bf16_t*>(p.ph[i].out);
-        e.ms[i] = p.ph[i].m;
-        e.metas[i] = mt;
-        e.inds[i] = ind;
-#pragma unroll
-        for (int k = 0; k < NE; k++) e.ld0[i][k] = e.ld1[i][k] = 0u;
-    }
-}
 template <int FORM, bool PRO = false>
 __global__ __launch_bounds__(kBlock, (FORM == 3 || PRO) ? 1 : 2) void k_gemm_mfma_epilogue(GemvEpiArgs p) {
     static_assert(!PRO || FORM <= 2, "a prologue exists for the forms with one tile of rows per workgroup");
-    const bf16_t* W = static_cast<const bf16_t*>(resolve_rt(p.g.W, p.head & 1u));
-    // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where workgroup 0 stores it
-    const bf16_t* h = static_cast<const bf16_t*>(PRO ? resolve_rt(p.x, p.head & kEpiXSlot) : resolve_rt(p.g.h, p.head & 2u));
-    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(resolve_rt(p.gain, p.head & kEpiGainSlot)) : nullptr;
+    // As in k_gemv_epilogue: the first 64 bytes of the arguments hold everything that is needed before the
+    // loads of h and the weights can go out, and only those are waited for here, in one batch of scalar loads;
+    // the epilogue's table and eps are read once the weights are on their way (MmEpilogue::prepare).
+    static_assert(offsetof(GemvEpiArgs, gain) + sizeof(void*) == 64, "what the kernel needs first sits in the first 64 bytes");
+    const void* Wa = p.g.W;
+    const void* ha = p.g.h;
+    bf16_t* y = static_cast<bf16_t*>(p.g.out);
+    int rows = p.g.rows, n = p.g.n, cols = p.g.cols, row_groups = p.g.row_groups;
+    unsigned head = p.head;
+    int n_epi = p.n_epi;
+    const void* xa = p.x;
+    const void* ga = p.gain;
+    asm volatile("" : "+s"(Wa), "+s"(ha), "+s"(y), "+s"(rows), "+s"(n), "+s"(cols), "+s"(row_groups), "+s"(head), "+s"(n_epi), "+s"(xa), "+s"(ga));
+    const void PG_CONSTANT* const ka = (const void PG_CONSTANT*)__builtin_amdgcn_kernarg_segment_ptr();   // a readable address for a load whose result is not used
+    using SlotPtr = const void* const PG_CONSTANT*;
+    auto slot_addr = [&](const void* q, bool is_slot) -> SlotPtr { return is_slot ? (SlotPtr)(uintptr_t)q : (SlotPtr)ka; };
+    // with a prologue the GEMV's input is computed from x and the gain; p.g.h is where the normalised rows are stored
+    if (head & (1u | (PRO ? kEpiXSlot | kEpiGainSlot : 2u))) {      // some operand is a pointer-table slot: all in one batch, without branches
+        const bool sw = head & 1u, sh = head & (PRO ? kEpiXSlot : 2u), sg = PRO && (head & kEpiGainSlot);
+        SlotPtr aw = slot_addr(Wa, sw), ah = slot_addr(PRO ? xa : ha, sh), ag = slot_addr(ga, sg);
+        const void* tw = *aw;
+        const void* th = *ah;
+        const void* tg = PRO ? *ag : nullptr;
+        asm volatile("" : "+s"(tw), "+s"(th), "+s"(tg));
+        if (sw) Wa = tw;
+        if (sh) { if (PRO) xa = th; else ha = th; }
+        if (sg) ga = tg;
+    }
+    const bf16_t* W = static_cast<const bf16_t*>(Wa);
+    const bf16_t* h = static_cast<const bf16_t*>(PRO ? xa : ha);
+    const bf16_t* gain = PRO ? static_cast<const bf16_t*>(ga) : nullptr;
     // the narrow forms have one workgroup per column block: the first stores; the 16-column form picks its column block 0 itself
-    bf16_t* hstore = (PRO && (p.head & kEpiStoreH) && (FORM == 2 || blockIdx.x == 0)) ? static_cast<bf16_t*>(const_cast<void*>(p.g.h)) : nullptr;
+    bf16_t* hstore = (PRO && (head & kEpiStoreH) && (FORM == 2 || blockIdx.x == 0)) ? static_cast<bf16_t*>(const_cast<void*>(ha)) : nullptr;
     __shared__ __attribute__((aligned(16))) char stage[4 * kMmWaveLds];
     __shared__ float red[(FORM == 3 ? 2 : 1) * 4 * 64 * 4];
-    MmEpilogue<FORM == 3 ? 2 : 1> emit;
-    mm_epilogue_setup(p, emit);
+    MmEpilogue<FORM == 3 ? 2 : 1, FORM <= 1> emit;
+    emit.y = y; emit.rows = rows; emit.n = n; emit.head = head; emit.n_epi = n_epi; emit.ka = ka;
     const bool al = aligned_to(W, 16) && aligned_to(h, 16) && (!PRO || aligned_to(gain, 16));
     if constexpr (FORM == 0) {
-        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 8, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
-        else gemm_mfma_narrow_body<true, false, 8, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 8, PRO>(W, h, emit, rows, n, cols, stage, red, gain, emit.eps, hstore);
+        else gemm_mfma_narrow_body<true, false, 8, PRO>(W, h, emit, rows, n, cols, stage, red, gain, emit.eps, hstore);
     } else if constexpr (FORM == 1) {
-        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
-        else gemm_mfma_narrow_body<true, false, 16, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, stage, red, gain, p.eps, hstore);
+        if (__builtin_expect(al, 1)) gemm_mfma_narrow_body<true, true, 16, PRO>(W, h, emit, rows, n, cols, stage, red, gain, emit.eps, hstore);
+        else gemm_mfma_narrow_body<true, false, 16, PRO>(W, h, emit, rows, n, cols, stage, red, gain, emit.eps, hstore);
     } else if constexpr (FORM == 2) {
-        if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red, gain, p.eps, hstore);
-        else gemm_mfma_body<true, true, false, PRO>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red, gain, p.eps, hstore);
+        if (__builtin_expect(al, 1)) gemm_mfma_body<true, true, true, PRO>(W, h, emit, rows, n, cols, row_groups, stage, red, gain, emit.eps, hstore);
+        else gemm_mfma_body<true, true, false, PRO>(W, h, emit, rows, n, cols, row_groups, stage, red, gain, emit.eps, hstore);
     } else {
-        if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
-        else gemm_mfma_wide_body<false>(W, h, emit, p.g.rows, p.g.n, p.g.cols, p.g.row_groups, stage, red);
+        if (__builtin_expect(al, 1)) gemm_mfma_wide_body<true>(W, h, emit, rows, n, cols, row_groups, stage, red);
+        else gemm_mfma_wide_body<false>(W, h, emit, rows, n, cols, row_groups, stage, red);
     }
 }
 
