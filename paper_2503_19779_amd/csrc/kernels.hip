@@ -878,7 +878,7 @@ constexpr int kMmSteps = 16;        // K-steps per wave per super-chunk (4 waves
 constexpr int kMmSlotBytes = 272;   // 16 rows x 16 B + 16 B of padding
 constexpr int kMmWaveLds = 64 * kMmSlotBytes;   // one wave's staging area: one tile, 64 slots
 constexpr int kMmMaxRowGroups = 4;
-constexpr int kMmWideRows = 64;     // rows from which the 32-column form is used
+constexpr int kMmWideRows = 81;     // rows from which the 32-column form is used (measured: the 16-column form is faster up to 5 tiles of rows, slower from 6)
 
 // k offset of the 16-byte chunk that lane `l` of wave `wave` loads from a row (super-chunk at step s0);
 // the same chunk is fragment step l >> 2, k-chunk l & 3 of that wave.
@@ -1385,7 +1385,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_mfma_bf16_narrow(GemvArgs p)
 
 // Wide form for many rows and cols == 2048: 32 output columns per workgroup, i.e. two sets of weight
 // fragments and two accumulators against every staged tile of h, which halves the h traffic per
-// output (the bound once rows >= 64).  One workgroup per CU (the fragments of 32 columns do not fit
+// output (the bound once there are many rows).  One workgroup per CU (the fragments of 32 columns do not fit
 // the register budget of two), waves 0 and 1 each finish one 16-column half.
 template <bool AL, class Emit>
 __device__ __forceinline__ void gemm_mfma_wide_body(const bf16_t* W, const bf16_t* h, Emit& emit, int rows, int n, int cols, int row_groups,

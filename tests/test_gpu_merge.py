@@ -26,7 +26,7 @@ def _all_modes(h, x_dev):
     return outs
 
 
-@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8, 13, 16, 17, 24, 32, 48, 63, 64, 100, 128])
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8, 13, 16, 17, 24, 32, 48, 63, 64, 72, 80, 81, 100, 128])
 def test_merged_graphs_equal_eager_and_unmerged_graphs(batch):
     spec = decode_chain(batch=batch, layers=3, blocks_per_layer=4, hidden=2048, n_ext=6)
     h = Harness(spec, capture=False)
@@ -191,7 +191,7 @@ def test_prologue_with_other_output_widths(rows, n):
 
 
 @pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100),
-                                    (5, 1027), (8, 2048), (13, 1030), (16, 40), (17, 1100), (40, 1029), (63, 48), (64, 1030), (100, 2048), (130, 70)])
+                                    (5, 1027), (8, 2048), (13, 1030), (16, 40), (17, 1100), (40, 1029), (63, 48), (64, 1030), (70, 1030), (80, 2048), (81, 40), (100, 2048), (130, 70)])
 def test_gemv_with_elementwise_epilogue(rows, n):
     """A GEMV (ragged last workgroup for odd n) followed by GELU in place, an add with an external operand,
     a mul with a broadcast weight and further kernels: the first three ride in the GEMV's dispatch, the rest

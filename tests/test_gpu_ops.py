@@ -153,6 +153,8 @@ def test_rmsnorm(dtype, rows, cols, off):
                                          (17, 16, 64), (2, 100, 2048), (130, 40, 2048), (128, 256, 2048), (33, 50, 8), (16, 31, 6152),
                                          # matrix-core form: several row groups, several K passes, ragged last tile and column block
                                          (40, 48, 4096), (100, 33, 2048), (64, 2048, 2048), (20, 16, 2056), (72, 24, 8200), (8, 64, 2048),
+                                         # the 16-column form with two tiles of rows per workgroup and an idle last row group; the first 32-column shape
+                                         (72, 100, 2048), (80, 2048, 2048), (81, 70, 2048),
                                          # one tile of rows: 8 columns per workgroup, with and without the upper half of the tile
                                          (16, 2048, 2048), (12, 100, 1024), (9, 20, 2048), (6, 16, 2040), (7, 27, 8), (3, 64, 2048), (4, 100, 512),
                                          (4, 15, 2048), (3, 40, 4096),
