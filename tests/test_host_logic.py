@@ -273,7 +273,7 @@ def _gemv_chain(dtype, rows, n, cols):
     return ChainSpec("g", [k], [TensorSpec(dtype, rows * cols)], [TensorSpec(dtype, rows * n)], [TensorSpec(dtype, n * cols)], [0])
 
 
-@pytest.mark.parametrize("rows,want", [(1, 256), (2, 256), (4, 256), (8, 256), (16, 256), (32, 256), (64, 256), (128, 256), (48, 384)])
+@pytest.mark.parametrize("rows,want", [(1, 256), (2, 256), (4, 256), (8, 256), (16, 256), (32, 256), (64, 512), (80, 512), (81, 256), (128, 256), (48, 384)])
 def test_decode_gemv_fills_the_chip_at_every_bucket(rows, want):
     """The 2048 x 2048 bf16 GEMV is laid out over at least one workgroup per CU (256) at every batch
     size: weight streaming needs every CU pulling (the shape is fixed on the host, so no GPU is needed
