@@ -1758,6 +1758,7 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
     unsigned ld0[P], ld1[P];
     bool mine = false;
     unsigned idx = 0;
+    bool decoder = false;       // the tail is GELU of the GEMV's result, then one or two adds with an operand from memory
     // The epilogue's operands: asked for once the weights are on their way (pointer-table slots first, with
     // scalar loads, all at once).  Always the same number of loads -- an operand that comes from a register
     // slot is fetched from the GEMV's own output buffer instead and ignored -- so that every wait on the
@@ -1794,6 +1795,16 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
         }
         any = __builtin_amdgcn_readfirstlane(any);
         asm volatile("" : "+s"(any));       // keeps what follows behind the weight loads
+        {   // the decoder block's tail, recognised here (scalar arithmetic under the weights' latency) so that the
+            // tail itself runs it straight through, without the operand and slot selection of the general form
+            auto add_of = [](unsigned mt, unsigned q) {
+                const unsigned a = (mt >> 8) & 0xffu, b = (mt >> 16) & 0xffu;
+                return (mt & 0xffu) == (unsigned)kAdd && ((a == q && b == kMergeFromMemory) || (a == kMergeFromMemory && b == q));
+            };
+            const unsigned hq = (head >> 8) & 0xffu, d0 = metas[0] >> 24, d1 = metas[1] >> 24;
+            decoder = (n_epi == 2 || n_epi == 3) && (metas[0] & 0xffu) == (unsigned)kGelu && ((metas[0] >> 8) & 0xffu) == hq &&
+                      add_of(metas[1], d0) && (n_epi == 2 || add_of(metas[2], d1));
+        }
         if (any) {
             SlotPtr at0[P], at1[P];
             const void* t0[P];
@@ -1859,6 +1870,29 @@ __global__ __launch_bounds__(kBlock) void k_gemv_epilogue(GemvEpiArgs p) {
 #pragma unroll
         for (int q = 0; q < kMergeSlots; q++)
             if (dst == (unsigned)q) slot[q] = from_raw<bf16_t>(bits);
+    }
+    if (__builtin_expect(decoder, 1)) {
+        // the same kernels with the same arithmetic and roundings, operands known: GELU of the GEMV's rounded result,
+        // then each add takes the value before it and its operand from memory, in the order its descriptor names
+        const bool st = mine;
+        float val = ew_apply<kGelu, false>(from_raw<bf16_t>(bits), 0.f);
+        bits = f32_to_bf16(val);
+        if (st && (inds[0] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[0] + idx) = (unsigned short)bits;
+        val = from_raw<bf16_t>(bits);
+        {
+            const bool mem_first = ((metas[1] >> 8) & 0xffu) == kMergeFromMemory;
+            const float fa = mem_first ? from_raw<bf16_t>(ld0[1]) : val, fb = mem_first ? val : from_raw<bf16_t>(ld1[1]);
+            bits = f32_to_bf16(ew_apply<kAdd, false>(fa, fb));
+            if (st && (inds[1] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[1] + idx) = (unsigned short)bits;
+            val = from_raw<bf16_t>(bits);
+        }
+        if (n_epi == 3) {
+            const bool mem_first = ((metas[2] >> 8) & 0xffu) == kMergeFromMemory;
+            const float fa = mem_first ? from_raw<bf16_t>(ld0[2]) : val, fb = mem_first ? val : from_raw<bf16_t>(ld1[2]);
+            bits = f32_to_bf16(ew_apply<kAdd, false>(fa, fb));
+            if (st && (inds[2] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[2] + idx) = (unsigned short)bits;
+        }
+        return;
     }
     // Unrolled, with the one big choice (GELU or not) as the only branch inside a phase: a taken branch costs
     // this one-wave-per-SIMD tail more than a dozen arithmetic instructions.
