@@ -977,6 +977,7 @@ struct MmEpilogue {
     bf16_t* outs[P];
     unsigned ms[P], metas[P], inds[P];
     bool plain = true;          // EARLY: no operand has a broadcast period
+    bool decoder = false;       // the kernels are GELU of the GEMV's result, then one or two adds with an operand from memory
     // per call
     unsigned idx[NE];
     bool ok[NE];
@@ -1015,6 +1016,15 @@ struct MmEpilogue {
         }
         any = __builtin_amdgcn_readfirstlane(any);
         asm volatile("" : "+s"(any));       // keeps what follows behind the weight loads
+        {   // the decoder block's tail, recognised here so that end() runs it straight through (see k_gemv_epilogue)
+            auto add_of = [](unsigned mt, unsigned q) {
+                const unsigned a = (mt >> 8) & 0xffu, b = (mt >> 16) & 0xffu;
+                return (mt & 0xffu) == (unsigned)kAdd && ((a == q && b == kMergeFromMemory) || (a == kMergeFromMemory && b == q));
+            };
+            const unsigned hq = (head >> 8) & 0xffu, d0 = metas[0] >> 24, d1 = metas[1] >> 24;
+            decoder = (n_epi == 2 || n_epi == 3) && (metas[0] & 0xffu) == (unsigned)kGelu && ((metas[0] >> 8) & 0xffu) == hq &&
+                      add_of(metas[1], d0) && (n_epi == 2 || add_of(metas[2], d1));
+        }
         if (any) {                           // some operand is a pointer-table slot: all in one batch, without branches
             auto slot_addr = [&](const void* q, bool is_slot) -> SlotPtr { return is_slot ? (SlotPtr)(uintptr_t)q : (SlotPtr)ka; };
             SlotPtr at0[P], at1[P];
@@ -1100,6 +1110,30 @@ struct MmEpilogue {
         for (int e = 0; e < NE; e++) {
             bits[e] = f32_to_bf16(v[e]);
             if (ok[e] && (head & kEpiHeadStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(y + idx[e]) = (unsigned short)bits[e];
+        }
+        if (__builtin_expect(decoder, 1)) {
+            // the same kernels with the same arithmetic and roundings, operands known: GELU of the GEMV's rounded result,
+            // then each add takes the value before it and its operand from memory, in the order its descriptor names
+            const bool mf1 = ((metas[1] >> 8) & 0xffu) == kMergeFromMemory, mf2 = ((metas[2] >> 8) & 0xffu) == kMergeFromMemory;
+#pragma unroll
+            for (int e = 0; e < NE; e++) {
+                float val = ew_apply<kGelu, false>(from_raw<bf16_t>(bits[e]), 0.f);
+                unsigned b = f32_to_bf16(val);
+                if (ok[e] && (inds[0] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[0] + idx[e]) = (unsigned short)b;
+                val = from_raw<bf16_t>(b);
+                {
+                    const float fa = mf1 ? from_raw<bf16_t>(ld0[1][e]) : val, fb = mf1 ? val : from_raw<bf16_t>(ld1[1][e]);
+                    b = f32_to_bf16(ew_apply<kAdd, false>(fa, fb));
+                    if (ok[e] && (inds[1] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[1] + idx[e]) = (unsigned short)b;
+                    val = from_raw<bf16_t>(b);
+                }
+                if (n_epi == 3) {
+                    const float fa = mf2 ? from_raw<bf16_t>(ld0[2][e]) : val, fb = mf2 ? val : from_raw<bf16_t>(ld1[2][e]);
+                    b = f32_to_bf16(ew_apply<kAdd, false>(fa, fb));
+                    if (ok[e] && (inds[2] & kEpiStore)) *(unsigned short PG_GLOBAL*)(uintptr_t)(outs[2] + idx[e]) = (unsigned short)b;
+                }
+            }
+            return;
         }
         {
             const unsigned dst = (head >> 8) & 0xffu;
