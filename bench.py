@@ -225,7 +225,7 @@ def main() -> int:
                           list(spec.weights[:n_gemv]) + [TensorSpec("bf16", H), TensorSpec("bf16", H)], [0])
         gchain = pg.Chain(gspec, w_dev[:n_gemv] + [x_dev[0][0], w_dev[n_gemv]], dev)
         nodes = gchain.graph_dispatches()[0]
-        assert nodes == n_gemv + (1 if sub_block else 0), nodes      # an even number of sub-blocks: none is split (see DESIGN, renaming)
+        assert nodes == n_gemv + (1 if sub_block else 0), nodes      # an even number of renaming sub-blocks: none is split back into RMSNorm + GEMV dispatch
         gchain.capture(stream)
         for _ in range(5):
             gchain.replay_copy([], stream)
