@@ -190,6 +190,44 @@ def test_prologue_with_other_output_widths(rows, n):
     h.close()
 
 
+@pytest.mark.parametrize("rows", [1, 3, 6, 12, 20, 70, 100])
+@pytest.mark.parametrize("order", [0, 1])
+def test_decoder_tail_with_a_broadcast_operand_and_either_operand_order(rows, order):
+    """GEMV -> GELU -> add -> add, the tail of a decoder block, which the GEMV's dispatch recognises and plays
+    straight through: here the second add takes a bias with a period of one row, and the adds name their
+    operand from memory first (order 0) or second (order 1)."""
+    H = 2048
+    N = rows * H
+    X, Y, Z = 1, 0, 2
+    S = X if order == 0 else Z        # in place only over the first operand: with y named first the sum goes to a third buffer
+    ks = [KernelSpec("add", "bf16", X, (Ref(EXT, 1), Ref(EXT, 1)), N, m=N),                          # x = 2 e1
+          KernelSpec("gemv", "bf16", Y, (Ref(WEIGHT, 0), Ref(EXT, 0)), H, rows=rows, cols=H),        # y
+          KernelSpec("gelu", "bf16", Y, (Ref(INT, Y),), N),                                          # y = gelu(y)
+          KernelSpec("add", "bf16", S, (Ref(INT, X), Ref(INT, Y)) if order == 0 else (Ref(INT, Y), Ref(INT, X)), N, m=N),   # s = x + y / y + x
+          KernelSpec("add", "bf16", S, (Ref(INT, S), Ref(WEIGHT, 1)), N, m=H),                       # s += bias[col]: a period of one row
+          KernelSpec("gemv", "bf16", Y, (Ref(WEIGHT, 0), Ref(INT, S)), H, rows=rows, cols=H),        # a second block: reads s
+          KernelSpec("gelu", "bf16", Y, (Ref(INT, Y),), N),
+          KernelSpec("add", "bf16", Z if order == 0 else X, (Ref(EXT, 1), Ref(INT, Y)) if order == 0 else (Ref(INT, Y), Ref(EXT, 1)), N, m=N)]   # two kernels only
+    spec = ChainSpec(f"decoder_tail_{rows}_{order}", ks,
+                     [TensorSpec("bf16", N), TensorSpec("bf16", N)],
+                     [TensorSpec("bf16", N), TensorSpec("bf16", N), TensorSpec("bf16", N)],
+                     [TensorSpec("bf16", H * H, ("normal", 0.0, 0.02)), TensorSpec("bf16", H, ("normal", 0.0, 0.5))],
+                     [0, 1, 2], 6030)
+    h = Harness(spec, capture=False)
+    merged, unmerged = h.chain.graph_dispatches()
+    say(f"{spec.name}: {unmerged} kernels in {merged} dispatches")
+    assert merged == 3, (merged, unmerged)      # [add] [GEMV, GELU, add, add] [GEMV, GELU, add]
+    h.chain.capture(h.stream)
+    for t in range(3):
+        x_np, x_dev = h.inputs(t)
+        outs = _all_modes(h, x_dev)
+        for o in range(len(spec.outputs)):
+            assert same_bits(outs["eager"][o], outs["copy"][o]) and same_bits(outs["eager"][o], outs["indirect"][o]), (t, o)
+        h.scrub()
+        stepwise_check(h, x_np, x_dev)
+    h.close()
+
+
 @pytest.mark.parametrize("rows,n", [(1, 1027), (2, 2048), (3, 1030), (4, 1100),
                                     (5, 1027), (8, 2048), (13, 1030), (16, 40), (17, 1100), (40, 1029), (63, 48), (64, 1030), (70, 1030), (80, 2048), (81, 40), (100, 2048), (130, 70)])
 def test_gemv_with_elementwise_epilogue(rows, n):
