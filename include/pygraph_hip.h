@@ -262,7 +262,8 @@ pg_status pg_set_copy_refresh(pg_chain *chain, int32_t how /* pg_copy_refresh */
  * element over the same n elements (a whole number of 16-byte vectors; fp32 tensors of up to 16384
  * elements are worked one element per lane instead, with any n, and only there the fp32 GELU takes
  * part).  A lane runs the kernels in order on its elements with their stand-alone arithmetic and one
- * rounding each, stores every kernel's output, and hands the stored bits to the next kernel in registers, so
+ * rounding each, stores every kernel's output that no later kernel of the run overwrites, and hands the stored
+ * bits to the next kernel in registers, so
  * results stay bit-identical to eager launches.  A run ends where a kernel reads something an earlier
  * kernel of the run wrote in any other pattern than element for element.  Likewise up to 3 elementwise
  * kernels over the outputs of a bf16 GEMV over rows of 2048 columns (GELU of the result, the residual

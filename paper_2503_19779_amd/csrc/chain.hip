@@ -890,7 +890,7 @@ pg_status capture_segment(pg_chain* c, Segment& sg, int kind, int inst, hipStrea
             ph.m = (d.op == PG_ADD || d.op == PG_MUL) ? (unsigned)(d.m ? d.m : d.n) : 0u;
             ph.eps = d.op == PG_RMSNORM ? d.eps : 0.f;
             ph.meta = (unsigned)d.op | ((unsigned)grp.src0[m.n_phase] << 8) | ((unsigned)grp.src1[m.n_phase] << 16) | ((unsigned)grp.dst[m.n_phase] << 24);
-            ph.ind = kind == kGraphCopy ? 0u : (unsigned)r.ind_mask;
+            ph.ind = (kind == kGraphCopy ? 0u : (unsigned)r.ind_mask) | (grp.store[m.n_phase] ? pgk::kEpiStore : 0u);
         }
         for (int q = m.n_phase; q < pgk::kMergeMaxPhases; q++) m.ph[q].meta = (unsigned)PG_GELU;   // operands "from slot 0": fetches nothing, never played
         le = launch(grp.launch, &m, s);

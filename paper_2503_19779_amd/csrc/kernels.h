@@ -77,7 +77,7 @@ struct TableArgs {
 // exactly 256 x 16 bytes -- goes out as ONE dispatch.  The tensor is cut into units of 256 lanes x 16
 // bytes (lane t owns vector t of a unit; an RMSNorm row is one unit), one workgroup per unit.  The lane
 // runs the kernels one after the other, each with its stand-alone arithmetic and its one rounding to
-// the storage type, stores every kernel's output, and hands the stored bits on to the next kernel in
+// the storage type, stores its output unless a later kernel of the run overwrites it, and hands the stored bits on to the next kernel in
 // registers when that kernel reads the same buffer element for element -- so the run costs one trip
 // to memory, not one per kernel.  Operands that no kernel of the run produces are fetched up front.
 constexpr int kMergeMaxPhases = 4;        // kernels per merged dispatch

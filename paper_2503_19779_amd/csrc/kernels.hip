@@ -1592,12 +1592,13 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
     const unsigned tid = threadIdx.x;
     // the run's table, once, in scalar registers (read inside the loop below it would be indexed memory)
     T* outs[P];
-    unsigned metas[P];
+    unsigned metas[P], inds[P];
     float epss[P];
 #pragma unroll
     for (int i = 0; i < P; i++) {
         outs[i] = static_cast<T*>(p.ph[i].out);
         metas[i] = p.ph[i].meta;
+        inds[i] = p.ph[i].ind;
         epss[i] = p.ph[i].eps;
     }
     const unsigned n = p.n, nvec = n / NV;
@@ -1644,11 +1645,61 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
     // sits at the head of the loop below and then also waits, every time round, for the store of the
     // kernel before (loads and stores of a wave share one counter): a microsecond per kernel.
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+    {   // A chain -- every kernel takes the result of the one before it (the first: memory) and, if it has a second
+        // operand, takes that from memory; no RMSNorm -- is played straight through: the choice of the operation is
+        // the only thing left to decide per kernel (the operand, slot and table selection of the general loop below
+        // and its taken branches cost a one-wave-per-SIMD kernel more than the arithmetic).  Same operations, same
+        // order, same roundings.
+        bool chain = n_phase >= 1;
+        unsigned prev = kMergeFromMemory;
+#pragma unroll
+        for (int i = 0; i < P; i++) {
+            const unsigned mt = metas[i], op = mt & 0xffu;
+            const bool in = i < n_phase;
+            chain = chain && (!in || (op != (unsigned)kRmsNorm && ((mt >> 8) & 0xffu) == prev && (op == (unsigned)kGelu || ((mt >> 16) & 0xffu) == kMergeFromMemory)));
+            prev = mt >> 24;
+        }
+        if (chain) {
+            unsigned w[NW];
+#pragma unroll
+            for (int k = 0; k < NW; k++) w[k] = ld0[0][k];
+#pragma unroll
+            for (int i = 0; i < P; i++) {
+                if (i >= n_phase) break;
+                const unsigned op = metas[i] & 0xffu;
+                float fa[NV], fb[NV], fo[NV];
+                V::unpack(w, fa);
+                V::unpack(ld1[i], fb);
+                if (op == (unsigned)kGelu) {
+                    if constexpr (!kWide || VB == 4) {
+#pragma unroll
+                        for (int e = 0; e < NV; e++) fo[e] = ew_apply<kGelu, kWide>(fa[e], 0.f);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < NV; e++) fo[e] = fa[e];      // never planned: the fp32 GELU rides only one element per lane
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < NV; e++) {
+                        const float sum = ew_apply<kAdd, kWide>(fa[e], fb[e]), prod = ew_apply<kMul, kWide>(fa[e], fb[e]);
+                        fo[e] = op == (unsigned)kAdd ? sum : prod;
+                    }
+                }
+                V::pack(fo, w);
+                if (act && (inds[i] & kEpiStore)) {
+                    if constexpr (VB == 16) store_vec_global(outs[i] + i0, w);
+                    else *(unsigned PG_GLOBAL*)(uintptr_t)(outs[i] + i0) = w[0];
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll 1
     for (int i = 0; i < n_phase; i++) {
         // this kernel's entry of the table and its fetched operands: uniform selects, no indexing
         T* out = outs[0];
         unsigned mt = metas[0];
+        unsigned ind = inds[0];
         float eps = epss[0];
         unsigned wa[NW], wb[NW], wo[NW];
 #pragma unroll
@@ -1656,7 +1707,7 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
 #pragma unroll
         for (int j = 1; j < P; j++)
             if (i == j) {
-                out = outs[j]; mt = metas[j]; eps = epss[j];
+                out = outs[j]; mt = metas[j]; ind = inds[j]; eps = epss[j];
 #pragma unroll
                 for (int k = 0; k < NW; k++) { wa[k] = ld0[j][k]; wb[k] = ld1[j][k]; }
             }
@@ -1701,7 +1752,7 @@ __device__ __forceinline__ void merged_body(const MergedArgs& p, const T* const*
             }
         }
         V::pack(fo, wo);
-        if (act) {
+        if (act && (ind & kEpiStore)) {      // not stored: a later kernel of the run overwrites it, and nothing reads memory in between
             if constexpr (VB == 16) store_vec_global(out + i0, wo);
             else *(unsigned PG_GLOBAL*)(uintptr_t)(out + i0) = wo[0];
         }
